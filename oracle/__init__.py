@@ -1,0 +1,13 @@
+"""WKV6 prefill oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It shares no code with the GPU library
+and never imports it.
+
+``wkv6_oracle``   sequential fp64 recurrence in plain C (``wkv6_oracle.c``),
+                  threaded over (batch, head) units.
+``wkv6_numpy``    an independent NumPy fp64 twin of the same recurrence
+                  (``wkv6_numpy.py``), used to cross-check the C build.
+"""
+from .cbuild import build_oracle, wkv6_oracle  # noqa: F401
+from .wkv6_numpy import wkv6_numpy  # noqa: F401
