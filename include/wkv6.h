@@ -1,0 +1,120 @@
+/*
+ * wkv6.h -- C ABI of the MI355X (gfx950) WKV6 prefill library.
+ *
+ * One call evaluates, for one layer and every (batch b, head h) independently,
+ * the Finch (RWKV-6) time-mix recurrence that GoldFinch's linear-time pre-fill
+ * runs in each Finch / Finch-C2 layer (paper: Method, "Finch-C2 Time Mixing":
+ * decay map w_t = exp(-exp(d_t)); state wkv_t = sum_{i<t} diag(prod_{j=i+1}^{t-1}
+ * w_j) k_i^T v_i; read-out r_t . wkv_t; and "Pre-fill of the compressed key
+ * cache ..." for why this is the pre-fill hot loop):
+ *
+ *     o_t = r_t . ( S_{t-1} + diag(u) k_t^T v_t )      t = 1..T
+ *     S_t = diag(w_t) S_{t-1} + k_t^T v_t ,            w_t = exp(-exp(x_t))
+ *
+ * S is a (key channel i) x (value channel j) matrix per (b,h); the decay acts
+ * on the key channel; S_0 is `state_in` (or zero); `u` is the per-head Finch
+ * bonus.  Finch-C2 is the case u = 0 with the caller scaling k by (1 - w) and
+ * adding its second value u'_t to the output.
+ *
+ * Argument meaning and layout (all tensors row-major, innermost index last):
+ *   B, T, H, N   batch, tokens per sequence, heads, head size.  N must be 64.
+ *                B = 0 is a no-op; T = 0 writes state_out = S_0 and no output.
+ *   r, k, v, x   [B][T][H][N]  receptance, key, value, decay logit (x = d_t)
+ *   u            [H][N]        fp32 bonus
+ *   state_in     [B][H][N][N]  fp32, [key i][value j]; NULL means S_0 = 0 (not read)
+ *   out          [B][T][H][N]  o_t
+ *   state_out    [B][H][N][N]  fp32 S_T; NULL means "do not write".  May equal
+ *                              state_in (updated in place).  `out` must not alias
+ *                              any input.
+ *   stream       a hipStream_t passed as void* (NULL = the default stream)
+ *
+ * Ownership: every pointer is a DEVICE pointer owned by the caller; base
+ * addresses of r,k,v,x,out must be 16-byte aligned.  Unless an entry point's own
+ * comment says otherwise the library allocates nothing, keeps no state between
+ * calls, only enqueues work on `stream` and never synchronises, so calls on
+ * different streams may overlap.
+ *
+ * Decay logits: any finite x, and x = -inf (w = 1) and x = +inf (w = 0), are
+ * handled exactly as the formula says: the chunked kernels only ever form
+ * products of decays (all <= 1), never a reciprocal, so there is no clamp.
+ *
+ * Value range of the bf16 entry points: the dense contractions run on the
+ * matrix cores with fp16 operands and fp32 accumulation; r, k, v and the
+ * running state must stay below 65504 in magnitude (larger values saturate to
+ * that bound).  The fp32 entry point has no such limit.
+ *
+ * Errors: every entry point returns a wkv6_status.  Arguments are validated
+ * before anything is enqueued; on a non-zero status nothing was launched,
+ * except WKV6_ERR_LAUNCH which reports the HIP runtime refusing a launch.
+ */
+#ifndef WKV6_H
+#define WKV6_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WKV6_OK = 0,
+    WKV6_ERR_NULL = 1,        /* a required pointer is NULL */
+    WKV6_ERR_SHAPE = 2,       /* negative size, H < 1, stride too small, overflow of the grid */
+    WKV6_ERR_UNSUPPORTED = 3, /* N != 64, or an unknown dtype code */
+    WKV6_ERR_LAUNCH = 4,      /* hipGetLastError() after the launch was not hipSuccess */
+    WKV6_ERR_ALIGN = 5        /* a tensor base or the batch stride is not 16-byte aligned */
+} wkv6_status;
+
+typedef enum {
+    WKV6_DTYPE_BF16 = 0,
+    WKV6_DTYPE_F32 = 1
+} wkv6_dtype;
+
+/* bf16 r,k,v,x; fp32 u and state; bf16 out.  Chunked matrix-core kernel. */
+int wkv6_prefill_bf16(int B, int T, int H, int N,
+                      const void *r, const void *k, const void *v, const void *x,
+                      const float *u, const float *state_in,
+                      void *out, float *state_out, void *stream);
+
+/* Same computation, `out` written in fp32 (no final rounding of the output). */
+int wkv6_prefill_bf16_f32out(int B, int T, int H, int N,
+                             const void *r, const void *k, const void *v, const void *x,
+                             const float *u, const float *state_in,
+                             float *out, float *state_out, void *stream);
+
+/*
+ * As above for a window of a larger [B][T_full][H][N] buffer: consecutive
+ * batches of r,k,v,x,out are `batch_stride` ELEMENTS apart (>= T*H*N, multiple
+ * of 8) while tokens stay H*N apart.  Lets a caller run tokens [t0,t1) of every
+ * sequence with a carried state.  out_dtype is a wkv6_dtype.
+ */
+int wkv6_prefill_bf16_strided(int B, int T, int H, int N,
+                              const void *r, const void *k, const void *v, const void *x,
+                              const float *u, const float *state_in,
+                              void *out, float *state_out,
+                              long long batch_stride, int out_dtype, void *stream);
+
+/* All-fp32 tensors.  Token-by-token kernel with the state in fp32 registers. */
+int wkv6_prefill_f32(int B, int T, int H, int N,
+                     const float *r, const float *k, const float *v, const float *x,
+                     const float *u, const float *state_in,
+                     float *out, float *state_out, void *stream);
+
+/*
+ * bf16 inputs, fp32 out, evaluated by the token-by-token fp32 kernel instead of
+ * the chunked one (same recurrence, no matrix cores, no fp16 operands): the
+ * on-device cross-check and the "before" number of the benchmark.
+ */
+int wkv6_prefill_bf16_recurrent(int B, int T, int H, int N,
+                                const void *r, const void *k, const void *v, const void *x,
+                                const float *u, const float *state_in,
+                                float *out, float *state_out, void *stream);
+
+/* Human-readable name of a wkv6_status (static storage, never NULL). */
+const char *wkv6_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int wkv6_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WKV6_H */

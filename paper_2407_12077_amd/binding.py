@@ -1,0 +1,105 @@
+"""Thin ctypes binding of ``libwkv6.so``: argument marshalling only.
+
+Every entry point has the name and argument order of ``include/wkv6.h``.  Tensors are
+PyTorch-ROCm tensors used purely as device memory (``data_ptr``) and the current HIP
+stream; nothing is computed here.  There is no fallback: if the library is missing,
+loading raises.
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libwkv6.so")
+
+WKV6_OK = 0
+WKV6_DTYPE_BF16 = 0
+WKV6_DTYPE_F32 = 1
+
+EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_strided",
+           "wkv6_prefill_f32", "wkv6_prefill_bf16_recurrent", "wkv6_status_string",
+           "wkv6_version")
+
+_lib = None
+
+
+class Wkv6Error(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"wkv6 status {status}: {text}")
+        self.status = status
+
+
+def load():
+    """Load the C-ABI library built by ``paper_2407_12077_amd.build`` (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: run `python -m paper_2407_12077_amd.build` first")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i, ll = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
+        common = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
+        for name in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_f32",
+                     "wkv6_prefill_bf16_recurrent"):
+            fn = getattr(lib, name)
+            fn.restype = i
+            fn.argtypes = common + [vp]
+        lib.wkv6_prefill_bf16_strided.restype = i
+        lib.wkv6_prefill_bf16_strided.argtypes = common + [ll, i, vp]
+        lib.wkv6_status_string.restype = ctypes.c_char_p
+        lib.wkv6_status_string.argtypes = [i]
+        lib.wkv6_version.restype = i
+        lib.wkv6_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def status_string(status):
+    return load().wkv6_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is not None:
+        return ctypes.c_void_p(int(stream))
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status):
+    if status != WKV6_OK:
+        raise Wkv6Error(status, status_string(status))
+
+
+def _call(name, B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream, *extra):
+    fn = getattr(load(), name)
+    _check(fn(B, T, H, N, _ptr(r), _ptr(k), _ptr(v), _ptr(x), _ptr(u), _ptr(state_in),
+              _ptr(out), _ptr(state_out), *extra, _stream(stream)))
+
+
+def wkv6_prefill_bf16(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):
+    _call("wkv6_prefill_bf16", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream)
+
+
+def wkv6_prefill_bf16_f32out(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):
+    _call("wkv6_prefill_bf16_f32out", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream)
+
+
+def wkv6_prefill_bf16_strided(B, T, H, N, r, k, v, x, u, state_in, out, state_out,
+                              batch_stride, out_dtype, stream=None):
+    _call("wkv6_prefill_bf16_strided", B, T, H, N, r, k, v, x, u, state_in, out, state_out,
+          stream, ctypes.c_longlong(batch_stride), int(out_dtype))
+
+
+def wkv6_prefill_f32(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):
+    _call("wkv6_prefill_f32", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream)
+
+
+def wkv6_prefill_bf16_recurrent(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):
+    _call("wkv6_prefill_bf16_recurrent", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream)
+
+
+def wkv6_version():
+    return load().wkv6_version()

@@ -1,0 +1,25 @@
+"""Build ``libwkv6.so`` (HIP kernels + C ABI) for gfx950, in-tree, with hipcc."""
+import os
+import subprocess
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(PKG, "csrc")
+LIB = os.path.join(PKG, "libwkv6.so")
+SOURCES = ["wkv6_api.hip", "wkv6_recurrent.hip", "wkv6_chunked.hip"]
+# packed-fp32 VALU forms are switched off on purpose for the whole library
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def build(verbose=False, extra=()):
+    """Compile every source into one shared library; always recompiles."""
+    cmd = ["hipcc", *FLAGS, *extra, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.check_call(cmd)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,48 @@
+"""Helpers shared by the GPU tests: upload seeded inputs, call the C ABI through the thin
+binding, download, and compare with the oracle using the max-normalised error."""
+import numpy as np
+import torch
+
+import paper_2407_12077_amd as wkv
+
+TOL_BF16 = 2e-3     # bf16 inputs, fp32 output and state, vs the fp64 oracle
+TOL_F32 = 1e-5      # fp32 tensors
+BF16_OUT_ROUNDING = 2.0 ** -8   # extra allowance when the output itself is rounded to bf16
+
+
+def max_norm_err(got, ref):
+    """max |got - ref| / max |ref|  (the tolerance's definition of relative error)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    denom = np.abs(ref).max()
+    if denom == 0:
+        return float(np.abs(got).max())
+    return float(np.abs(got - ref).max() / denom)
+
+
+def to_dev(a, dtype):
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(dtype).cuda()
+
+
+def run_entry(entry, inp, out_dtype=torch.float32, in_dtype=torch.bfloat16, want_state=True,
+              inplace_state=False):
+    """Run one entry point on the arrays of ``inp`` (dict from make_inputs).  Returns
+    (out, state_out) as float64 NumPy arrays (state_out None if not requested)."""
+    B, T, H, N = inp["r"].shape
+    r, k, v, x = (to_dev(inp[n], in_dtype) for n in ("r", "k", "v", "x"))
+    u = to_dev(inp["u"], torch.float32)
+    s_in = to_dev(inp.get("state_in"), torch.float32)
+    out = torch.full((B, T, H, N), float("nan"), dtype=out_dtype, device="cuda")
+    if inplace_state:
+        assert s_in is not None
+        s_out = s_in
+    else:
+        s_out = torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda") if want_state else None
+    getattr(wkv, entry)(B, T, H, N, r, k, v, x, u, s_in, out, s_out)
+    torch.cuda.synchronize()
+    o = out.float().cpu().numpy().astype(np.float64)
+    s = None if s_out is None else s_out.cpu().numpy().astype(np.float64)
+    return o, s

@@ -1,0 +1,84 @@
+"""CPU-side checks of the boundary: the C-ABI library loads, exports every symbol the header
+declares, and rejects bad arguments before touching a GPU (validation runs first, so these
+calls enqueue nothing and need no device)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2407_12077_amd as wkv
+from paper_2407_12077_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "wkv6.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wkv6_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = header_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_status_strings():
+    assert wkv.wkv6_version() >= 100
+    assert wkv.status_string(0) == "ok"
+    for code in range(1, 6):
+        assert wkv.status_string(code) not in ("ok", "unknown status")
+    assert wkv.status_string(99) == "unknown status"
+
+
+def _raw(name):
+    return getattr(binding.load(), name)
+
+
+P = ctypes.c_void_p
+A = P(0x1000)          # aligned, never dereferenced: validation fails before any launch
+
+
+@pytest.mark.parametrize("name", ["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out",
+                                  "wkv6_prefill_f32", "wkv6_prefill_bf16_recurrent"])
+def test_validation_happens_before_any_launch(name):
+    f = _raw(name)
+    assert f(1, 8, 2, 32, A, A, A, A, A, None, A, A, None) == 3          # N != 64
+    assert f(-1, 8, 2, 64, A, A, A, A, A, None, A, A, None) == 2
+    assert f(1, -8, 2, 64, A, A, A, A, A, None, A, A, None) == 2
+    assert f(1, 8, 0, 64, A, A, A, A, A, None, A, A, None) == 2
+    assert f(1, 8, 2, 64, None, A, A, A, A, None, A, A, None) == 1
+    assert f(1, 8, 2, 64, A, A, A, A, None, None, A, A, None) == 1
+    assert f(1, 8, 2, 64, A, A, A, A, A, None, None, A, None) == 1
+    assert f(1, 8, 2, 64, P(0x1004), A, A, A, A, None, A, A, None) == 5
+    assert f(1, 8, 2, 64, A, A, A, A, A, P(0x1008), A, A, None) == 5
+    assert f(0, 8, 2, 64, None, None, None, None, A, None, None, None, None) == 0   # empty batch
+    assert f(70000, 8, 70000, 64, A, A, A, A, A, None, A, A, None) == 2              # grid overflow
+
+
+def test_strided_entry_validation():
+    f = _raw("wkv6_prefill_bf16_strided")
+    assert f(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64 - 8, 1, None) == 2   # stride < T*H*N
+    assert f(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64 + 4, 1, None) == 5   # stride % 8
+    assert f(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64, 7, None) == 3       # dtype code
+
+
+def test_binding_raises_with_status():
+    with pytest.raises(wkv.Wkv6Error) as e:
+        binding._check(3)
+    assert e.value.status == 3
+
+
+def test_oracle_is_not_reachable_from_the_product():
+    """The package must not import the oracle (no CPU fallback)."""
+    pkg = os.path.join(ROOT, "paper_2407_12077_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|libwkv6_oracle|wkv6_oracle", text, re.M), \
+                    f"{fn} reaches into the oracle"

@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle on the same
+seeded inputs.  Tolerances are the stated ones: max |gpu - oracle| / max |oracle| <= 2e-3
+for bf16 inputs (fp32 output and state) and <= 1e-5 for fp32 tensors.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_12077_amd as wkv
+from oracle import wkv6_oracle
+from paper_2407_12077_amd.workloads import CONFIGS, make_inputs, round_to_bf16, scaled
+
+from gpu_util import BF16_OUT_ROUNDING, TOL_BF16, TOL_F32, max_norm_err, run_entry, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def check(entry, inp, tol, **kw):
+    o_ref, s_ref = wkv6_oracle(inp["r"], inp["k"], inp["v"], inp["x"], inp["u"], inp.get("state_in"))
+    o, s = run_entry(entry, inp, **kw)
+    eo, es = max_norm_err(o, o_ref), max_norm_err(s, s_ref)
+    print(f"{entry}: shape={inp['r'].shape} err_out={eo:.3e} err_state={es:.3e}", flush=True)
+    assert np.isfinite(o).all() and np.isfinite(s).all()
+    assert eo <= tol, f"out error {eo:.3e} > {tol}"
+    assert es <= tol, f"state error {es:.3e} > {tol}"
+    return eo, es
+
+
+# ------------------------------------------------------------------ config 1 (fp32, full size)
+def test_config1_fp32_full(gpu_device):
+    inp = make_inputs(CONFIGS[1])
+    check("wkv6_prefill_f32", inp, TOL_F32, in_dtype=torch.float32)
+
+
+def test_fp32_with_initial_state_and_ragged_length(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[1], B=3, T=77, H=5, s0_std=0.5), seed=5)
+    check("wkv6_prefill_f32", inp, TOL_F32, in_dtype=torch.float32)
+
+
+def test_recurrent_kernel_on_bf16_inputs(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[2], B=2, T=300, H=3, s0_std=0.2), seed=6)
+    check("wkv6_prefill_bf16_recurrent", inp, TOL_F32)
+
+
+# ------------------------------------------------------------------ chunked kernel, oracle-sized
+@pytest.mark.parametrize("T", [1, 2, 7, 8, 9, 15, 16, 17, 31, 33, 63, 64, 65, 127, 128, 129, 200, 1000])
+def test_chunked_lengths(gpu_device, T):
+    inp = make_inputs(scaled(CONFIGS[2], B=2, T=T, H=3), seed=100 + T)
+    check("wkv6_prefill_bf16_f32out", inp, TOL_BF16)
+
+
+@pytest.mark.parametrize("cfg_index", [2, 4, 5])
+def test_chunked_reduced_configs(gpu_device, cfg_index):
+    cfg = CONFIGS[cfg_index]
+    inp = make_inputs(scaled(cfg, B=2, T=777, H=min(cfg.H, 8)))
+    check("wkv6_prefill_bf16_f32out", inp, TOL_BF16)
+
+
+def test_chunked_bf16_output(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[2], B=2, T=333, H=4, s0_std=0.1), seed=21)
+    o_ref, s_ref = wkv6_oracle(**inp)
+    o, s = run_entry("wkv6_prefill_bf16", inp, out_dtype=torch.bfloat16)
+    assert max_norm_err(s, s_ref) <= TOL_BF16
+    assert max_norm_err(o, o_ref) <= TOL_BF16 + BF16_OUT_ROUNDING
+    # against the oracle rounded the same way: the kernel's own share stays within tolerance
+    assert max_norm_err(o, round_to_bf16(o_ref.astype(np.float32))) <= TOL_BF16 + BF16_OUT_ROUNDING
+    o32, _ = run_entry("wkv6_prefill_bf16_f32out", inp)
+    assert np.array_equal(o, round_to_bf16(o32.astype(np.float32)).astype(np.float64))
+
+
+def test_chunked_matches_recurrent_kernel(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[4], B=3, T=512, H=4), seed=22)
+    o1, s1 = run_entry("wkv6_prefill_bf16_f32out", inp)
+    o2, s2 = run_entry("wkv6_prefill_bf16_recurrent", inp)
+    assert max_norm_err(o1, o2) <= TOL_BF16 and max_norm_err(s1, s2) <= TOL_BF16
+
+
+# ------------------------------------------------------------------ degenerate decays
+@pytest.mark.parametrize("xval", [-np.inf, np.inf, 20.0, -30.0, 3.0])
+@pytest.mark.parametrize("entry,tol,dt", [("wkv6_prefill_bf16_f32out", TOL_BF16, torch.bfloat16),
+                                          ("wkv6_prefill_f32", TOL_F32, torch.float32)])
+def test_constant_extreme_decay(gpu_device, xval, entry, tol, dt):
+    inp = make_inputs(scaled(CONFIGS[2], B=1, T=150, H=2, s0_std=0.3), seed=31)
+    inp["x"][:] = xval
+    check(entry, inp, tol, in_dtype=dt)
+
+
+def test_mixed_extreme_decays(gpu_device):
+    rng = np.random.default_rng(32)
+    inp = make_inputs(scaled(CONFIGS[2], B=2, T=260, H=2, s0_std=0.3), seed=32)
+    choices = np.array([-np.inf, np.inf, -20.0, 10.0, 0.0, -1.0, 2.0], dtype=np.float32)
+    inp["x"] = rng.choice(choices, size=inp["x"].shape).astype(np.float32)
+    check("wkv6_prefill_bf16_f32out", inp, TOL_BF16)
+    check("wkv6_prefill_bf16_recurrent", inp, TOL_F32)
+
+
+def test_zero_inputs_keep_decayed_state(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[2], B=1, T=100, H=2, s0_std=1.0), seed=33)
+    for n in ("r", "k", "v"):
+        inp[n][:] = 0
+    check("wkv6_prefill_bf16_f32out", inp, TOL_BF16)
+
+
+# ------------------------------------------------------------------ state handling through the ABI
+def test_state_passing_invariant_on_gpu(gpu_device):
+    """[0,T) in one call == [0,T1) then [T1,T) with the carried state (strided entry, B>1)."""
+    cfg = scaled(CONFIGS[2], B=3, T=448, H=4)
+    inp = make_inputs(cfg, seed=41)
+    B, T, H, N = inp["r"].shape
+    o_ref, s_ref = wkv6_oracle(**inp)
+    r, k, v, x = (to_dev(inp[n], torch.bfloat16) for n in "rkvx")
+    u = to_dev(inp["u"], torch.float32)
+    full_o = torch.empty((B, T, H, N), dtype=torch.float32, device="cuda")
+    full_s = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
+    wkv.wkv6_prefill_bf16_f32out(B, T, H, N, r, k, v, x, u, None, full_o, full_s)
+    for T1 in (64, 200, 447):
+        o = torch.full((B, T, H, N), float("nan"), dtype=torch.float32, device="cuda")
+        s = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
+        stride = T * H * N
+        wkv.wkv6_prefill_bf16_strided(B, T1, H, N, r, k, v, x, u, None, o, s, stride, wkv.WKV6_DTYPE_F32)
+        off = T1 * H * N
+        tail = lambda t: t.view(-1)[off:]            # same batch stride, window starts at token T1
+        wkv.wkv6_prefill_bf16_strided(B, T - T1, H, N, tail(r), tail(k), tail(v), tail(x), u, s,
+                                      tail(o), s, stride, wkv.WKV6_DTYPE_F32)   # state in place
+        torch.cuda.synchronize()
+        assert max_norm_err(o.cpu().numpy(), o_ref) <= TOL_BF16
+        assert max_norm_err(s.cpu().numpy(), s_ref) <= TOL_BF16
+        assert max_norm_err(o.cpu().numpy(), full_o.cpu().numpy()) <= TOL_BF16
+        assert max_norm_err(s.cpu().numpy(), full_s.cpu().numpy()) <= TOL_BF16
+
+
+def test_null_state_out_and_inplace_state(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[4], B=2, T=130, H=3), seed=42)
+    o_ref, s_ref = wkv6_oracle(**inp)
+    for entry, tol, dt in (("wkv6_prefill_bf16_f32out", TOL_BF16, torch.bfloat16),
+                           ("wkv6_prefill_bf16_recurrent", TOL_F32, torch.bfloat16)):
+        o, s = run_entry(entry, inp, want_state=False, in_dtype=dt)
+        assert s is None and max_norm_err(o, o_ref) <= tol
+        o, s = run_entry(entry, inp, inplace_state=True, in_dtype=dt)
+        assert max_norm_err(o, o_ref) <= tol and max_norm_err(s, s_ref) <= tol
+
+
+def test_empty_sequence_passes_state_through(gpu_device):
+    s_in = torch.randn(2, 3, 64, 64, device="cuda")
+    u = torch.zeros(3, 64, device="cuda")
+    s_out = torch.full_like(s_in, float("nan"))
+    wkv.wkv6_prefill_bf16_f32out(2, 0, 3, 64, None, None, None, None, u, s_in, None, s_out)
+    torch.cuda.synchronize()
+    assert torch.equal(s_in, s_out)
+    wkv.wkv6_prefill_f32(2, 0, 3, 64, None, None, None, None, u, None, None, s_out)
+    torch.cuda.synchronize()
+    assert (s_out == 0).all()
+    wkv.wkv6_prefill_bf16(0, 5, 3, 64, None, None, None, None, u, None, None, None)   # empty batch
+
+
+def test_runs_on_a_side_stream_and_is_deterministic(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[2], B=2, T=500, H=4), seed=43)
+    B, T, H, N = inp["r"].shape
+    r, k, v, x = (to_dev(inp[n], torch.bfloat16) for n in "rkvx")
+    u = to_dev(inp["u"], torch.float32)
+    outs = []
+    side = torch.cuda.Stream()
+    for i in range(3):
+        o = torch.empty((B, T, H, N), dtype=torch.float32, device="cuda")
+        s = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
+        if i == 2:
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                wkv.wkv6_prefill_bf16_f32out(B, T, H, N, r, k, v, x, u, None, o, s)
+            side.synchronize()
+        else:
+            wkv.wkv6_prefill_bf16_f32out(B, T, H, N, r, k, v, x, u, None, o, s)
+            torch.cuda.synchronize()
+        outs.append((o.cpu(), s.cpu()))
+    for o, s in outs[1:]:
+        assert torch.equal(o, outs[0][0]) and torch.equal(s, outs[0][1])     # bit-identical
+
+
+def test_finch_c2_reduction(gpu_device):
+    """u = 0 and k pre-multiplied by (1 - w): state rows stay normalised (each entry is a
+    convex combination of past values), so with v == 1 every state entry is 1 - prod w."""
+    rng = np.random.default_rng(44)
+    B, T, H, N = 1, 200, 2, 64
+    x = round_to_bf16(rng.uniform(-5, 0, (B, T, H, N)).astype(np.float32))
+    w = np.exp(-np.exp(x.astype(np.float64)))
+    k = round_to_bf16((1 - w).astype(np.float32))
+    inp = {"r": round_to_bf16(rng.standard_normal((B, T, H, N)).astype(np.float32) / 8), "k": k,
+           "v": np.ones((B, T, H, N), np.float32), "x": x, "u": np.zeros((H, N), np.float32),
+           "state_in": None}
+    _, s = check("wkv6_prefill_bf16_f32out", inp, TOL_BF16)
+    o, st = run_entry("wkv6_prefill_bf16_f32out", inp)
+    expect = 1 - np.prod(w, axis=1)[0]                       # [H, N(key)]
+    assert np.abs(st[0] - expect[:, :, None]).max() <= 3e-3  # k itself was rounded to bf16
+
+
+# ------------------------------------------------------------------ full-size configs, sampled units
+def _unit_slice(inp, b, h):
+    one = {n: np.ascontiguousarray(inp[n][b:b + 1, :, h:h + 1]) for n in "rkvx"}
+    one["u"] = np.ascontiguousarray(inp["u"][h:h + 1])
+    one["state_in"] = None if inp["state_in"] is None else np.ascontiguousarray(inp["state_in"][b:b + 1, h:h + 1])
+    return one
+
+
+@pytest.mark.parametrize("cfg_index,n_units", [(2, 12), (3, 3), (4, 48), (5, 6)])
+def test_full_size_config_sampled_units(gpu_device, cfg_index, n_units):
+    """The benchmark's launch configuration at BASELINE size; the oracle recomputes a seeded
+    sample of (batch, head) units in full (every token and the final state of each)."""
+    cfg = CONFIGS[cfg_index]
+    inp = make_inputs(cfg)
+    B, T, H, N = inp["r"].shape
+    r, k, v, x = (to_dev(inp[n], torch.bfloat16) for n in "rkvx")
+    u = to_dev(inp["u"], torch.float32)
+    s_in = to_dev(inp["state_in"], torch.float32)
+    out = torch.empty((B, T, H, N), dtype=torch.float32, device="cuda")
+    s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
+    wkv.wkv6_prefill_bf16_f32out(B, T, H, N, r, k, v, x, u, s_in, out, s_out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all() and torch.isfinite(s_out).all()
+    rng = np.random.default_rng(1000 + cfg_index)
+    units = {(0, 0), (B - 1, H - 1)}
+    while len(units) < n_units:
+        units.add((int(rng.integers(B)), int(rng.integers(H))))
+    worst_o = worst_s = 0.0
+    for (b, h) in sorted(units):
+        one = _unit_slice(inp, b, h)
+        o_ref, s_ref = wkv6_oracle(**one, nthreads=1)
+        eo = max_norm_err(out[b, :, h].cpu().numpy(), o_ref[0, :, 0])
+        es = max_norm_err(s_out[b, h].cpu().numpy(), s_ref[0, 0])
+        worst_o, worst_s = max(worst_o, eo), max(worst_s, es)
+    print(f"config {cfg_index}: {len(units)} units, worst err_out={worst_o:.3e} err_state={worst_s:.3e}", flush=True)
+    assert worst_o <= TOL_BF16 and worst_s <= TOL_BF16
+    if cfg_index == 3:
+        # state at T/2 and the state-passing invariant: two calls with the carried state
+        half = T // 2
+        o2 = torch.empty_like(out)
+        s_half = torch.empty_like(s_out)
+        s_end = torch.empty_like(s_out)
+        wkv.wkv6_prefill_bf16_f32out(B, half, H, N, r, k, v, x, u, None, o2, s_half)
+        off = half * H * N
+        tail = lambda t: t.view(-1)[off:]
+        wkv.wkv6_prefill_bf16_f32out(B, T - half, H, N, tail(r), tail(k), tail(v), tail(x), u, s_half,
+                                     tail(o2), s_end)
+        torch.cuda.synchronize()
+        assert max_norm_err(o2.cpu().numpy(), out.cpu().numpy()) <= 1e-6      # same chunk boundaries
+        assert max_norm_err(s_end.cpu().numpy(), s_out.cpu().numpy()) <= 1e-6
+        b, h = 0, 5
+        one = _unit_slice(inp, b, h)
+        for n in "rkvx":
+            one[n] = one[n][:, :half]
+        _, s_ref = wkv6_oracle(**one, nthreads=1)
+        assert max_norm_err(s_half[b, h].cpu().numpy(), s_ref[0, 0]) <= TOL_BF16
