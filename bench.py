@@ -1,0 +1,148 @@
+#!/usr/bin/env python3
+"""Benchmark of the WKV6 prefill hot path on one MI355X.
+
+A "step" is one `wkv6_prefill_bf16` call: one layer's WKV6 recurrence over one batch of
+synthetic Finch-1.6B-shaped inputs (B=8, T=4096, H=32, N=64, bf16 r/k/v/x, fp32 u and
+state, zero initial state, bf16 output and fp32 final state written).  Inputs are resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2..5] [--entry NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 MFMA
+
+# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each
+# scaled by the same counter's reading for a plain copy kernel); see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(cfg, out_bytes, state_in, state_out=True):
+    """Bytes the method must move per launch: r,k,v,x read once in bf16, the output written
+    once, plus the fp32 state of every (batch, head) unit read and/or written once."""
+    per_token_head = 4 * cfg.N * 2 + cfg.N * out_bytes
+    state = cfg.B * cfg.H * cfg.N * cfg.N * 4
+    return cfg.token_heads * per_token_head + state * (int(state_in) + int(state_out))
+
+
+def algorithmic_flops(cfg, chunk=64):
+    """Matrix-core flops of the chunked form per launch: 4*C*N + 4*N*N per token and head."""
+    return cfg.token_heads * (4 * chunk * cfg.N + 4 * cfg.N * cfg.N)
+
+
+def cpu_baseline(cfg, inp):
+    """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample."""
+    from oracle import wkv6_oracle
+    cores = min(os.cpu_count() or 1, 16)
+    budget_token_heads = 4_000_000              # about 10 s of CPU work on 8-16 cores
+    nb = max(1, min(cfg.B, budget_token_heads // (cfg.T * cfg.H)))
+    sample = {n: inp[n][:nb] for n in ("r", "k", "v", "x")}
+    s0 = None if inp["state_in"] is None else inp["state_in"][:nb]
+    t0 = time.perf_counter()
+    wkv6_oracle(sample["r"], sample["k"], sample["v"], sample["x"], inp["u"], s0, nthreads=cores)
+    dt = time.perf_counter() - t0
+    return {"value": nb * cfg.T / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {nb} of {cfg.B} sequences of the same workload "
+                      f"({nb * cfg.T * cfg.H} token-heads, fp64 sequential recurrence, {dt:.2f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
+    ap.add_argument("--entry", default="wkv6_prefill_bf16",
+                    choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards over (batch, head) "
+                 "with no communication; see DESIGN.md); use --gpus 1")
+
+    import torch
+    import paper_2407_12077_amd as wkv
+    from paper_2407_12077_amd.workloads import CONFIGS, make_inputs
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    wkv.load()                                   # fails loudly if the HIP library is missing
+    cfg = CONFIGS[args.config]
+    inp = make_inputs(cfg)
+    B, T, H, N = cfg.B, cfg.T, cfg.H, cfg.N
+
+    def dev(a, dt):
+        return None if a is None else torch.from_numpy(a).to(dt).cuda()
+
+    r, k, v, x = (dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "x"))
+    u = dev(inp["u"], torch.float32)
+    s_in = dev(inp["state_in"], torch.float32)
+    out_f32 = args.entry != "wkv6_prefill_bf16"
+    out = torch.empty((B, T, H, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
+    s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
+    fn = getattr(wkv, args.entry)
+
+    stream = torch.cuda.current_stream()         # the stream the kernels are launched on
+
+    def step():
+        fn(B, T, H, N, r, k, v, x, u, s_in, out, s_out, stream.cuda_stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # per-launch durations with HIP events on the launch stream, inside the timed region
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record(stream)
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
+    ms_per_step = wall * 1e3 / args.steps
+
+    abytes = algorithmic_bytes(cfg, 4 if out_f32 else 2, s_in is not None)
+    aflops = algorithmic_flops(cfg)
+    achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    key = f"config{args.config}:{args.entry}"
+    result = {
+        "metric": "WKV6 prefill tokens/s per layer (H=%d,N=%d,bf16)" % (H, N),
+        "value": B * T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 tensors; f16 MFMA operands, f32 accumulate and state"
+                 if args.entry != "wkv6_prefill_bf16_recurrent" else "bf16 tensors; f32 vector ALU",
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} ({cfg.name}): B={B} T={T} H={H} N={N}, "
+                               f"{'nonzero' if s_in is not None else 'zero'} initial state",
+                   "entry": args.entry, "global_batch": B, "seq_len": T},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(key),
+                     "kernel_ms_avg": kernel_ms, "kernel_ms_min": min(per_launch_ms),
+                     "algorithmic_bytes": abytes,
+                     "mfma_frac": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, inp)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
