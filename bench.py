@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--entry", default="wkv6_prefill_bf16",
                     choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain 512 MiB device copy (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over (batch, head) "
@@ -96,6 +98,12 @@ def main():
     def step():
         fn(B, T, H, N, r, k, v, x, u, s_in, out, s_out, stream.cuda_stream)
 
+    if args.copy_probe:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.bfloat16, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
