@@ -15,7 +15,7 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
         const float* u, const float* state_in, void* out, float* state_out,
         long long batch_stride, bool in_bf16, bool out_f32, Path path, void* stream) {
     if (N != wkv6::kHeadSize) return WKV6_ERR_UNSUPPORTED;
-    if (B < 0 || T < 0 || H < 1) return WKV6_ERR_SHAPE;
+    if (B < 0 || T < 0 || H < 1 || H > 262144) return WKV6_ERR_SHAPE;   // 32-bit row offsets in the kernels
     if (!u) return WKV6_ERR_NULL;
     if (B == 0) return WKV6_OK;
     const long long need = static_cast<long long>(T) * H * N;

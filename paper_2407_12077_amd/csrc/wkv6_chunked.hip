@@ -22,6 +22,15 @@
 // holds, row by row, the scaled key (rows in a first half) or the scaled receptance (rows in
 // a second half); one MFMA per level and 16x16 block followed by a select assembles the
 // score matrix.
+//
+// Work split inside the workgroup (12 wavefronts, 3 per SIMD):
+//   waves 0..7  "producers": stream r,k,v,x from HBM (prefetched one chunk ahead), compute
+//               decays and their products, write every fp16 operand tile to LDS, run the
+//               score MFMAs, and write the finished output tile to HBM with full-row stores;
+//   waves 8..11 "consumers": own 16 value columns of the state each and run the three
+//               state-dependent contractions, i.e. the only sequential chain of the method.
+// The two roles meet at three workgroup barriers per chunk; the producers work on the vector
+// ALUs while the consumers occupy the matrix cores of the same SIMDs.
 #include "wkv6_launch.h"
 
 namespace wkv6 {
@@ -30,14 +39,17 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
 constexpr int kChunk = 64;                 // tokens per chunk
-constexpr int kThreads = 256;              // 4 wavefronts
+constexpr int kProducerWaves = 8;
+constexpr int kConsumerWaves = 4;
+constexpr int kProducerThreads = 64 * kProducerWaves;
+constexpr int kThreads = 64 * (kProducerWaves + kConsumerWaves);
 constexpr int kRowHalfs = 72;              // fp16 tile row stride (64 + 8 pad) = 144 bytes
 constexpr int kTileBytes = 64 * kRowHalfs * 2;
-constexpr int kORow = 68;                  // fp32 output staging row stride (floats)
+constexpr int kORowF32 = 68;               // output staging row stride, fp32 mode (floats)
+constexpr int kORowBf16 = 72;              // output staging row stride, bf16 mode (halfs)
 
 // LDS map (bytes)
 enum : int {
@@ -53,10 +65,10 @@ enum : int {
     kKT = 9 * kTileBytes,      // (k * W(64,i))^T : [channel][token]
     kVT = 10 * kTileBytes,     // v^T            : [channel][token]
     kAT = 11 * kTileBytes,     // scores A[t][i]
-    kG = 12 * kTileBytes,                      // per 8-token group decay products [8][64] fp32
-    kD = kG + 8 * 64 * 4,                      // whole-chunk decay product [64] fp32
-    kO = kD + 64 * 4,                          // output staging [64][kORow] fp32
-    kLdsBytes = kO + 64 * kORow * 4
+    kG = 12 * kTileBytes,                      // per 4-token group decay products [16][64] fp32
+    kD = kG + 16 * 64 * 4,                     // whole-chunk decay product [64] fp32
+    kO = kD + 64 * 4,                          // output staging
+    kLdsBytes = kO + 64 * kORowF32 * 4
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -71,11 +83,8 @@ __device__ __forceinline__ unsigned pack_h2(float a, float b) {
     return __builtin_bit_cast(unsigned, p);
 }
 
-__device__ __forceinline__ unsigned pack_bf2(float a, float b) {
-    bf16x2 p;
-    p.x = static_cast<__bf16>(a);
-    p.y = static_cast<__bf16>(b);
-    return __builtin_bit_cast(unsigned, p);
+__device__ __forceinline__ unsigned short bf16_bits(float a) {
+    return __builtin_bit_cast(unsigned short, static_cast<__bf16>(a));
 }
 
 // w = exp(-exp(x)) through two base-2 exponentials (x=-inf -> 1, x=+inf -> 0).
@@ -87,281 +96,344 @@ __device__ __forceinline__ float decay_of(float x) {
 __device__ __forceinline__ half8 lds_read_h8(const char* lds, int byte_off) {
     return *reinterpret_cast<const half8*>(lds + byte_off);
 }
+__device__ __forceinline__ void lds_write_u32(char* lds, int byte_off, unsigned val) {
+    *reinterpret_cast<unsigned*>(lds + byte_off) = val;
+}
 
-struct Raw {           // one chunk's inputs of this thread: 8 tokens x one channel pair, bf16 bits
-    unsigned r[8], k[8], v[8], x[8];
+__device__ __forceinline__ float4v mfma(half8 a, half8 b, float4v c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+struct Raw {           // one chunk's inputs of a producer thread: 4 tokens x one channel pair
+    unsigned r[4], k[4], v[4], x[4];
 };
 
-__device__ __forceinline__ void load_chunk(Raw& d, const Args& a, long long base, int t0, int T,
-                                           long long tok_stride) {
-    const unsigned* pr = static_cast<const unsigned*>(a.r);
-    const unsigned* pk = static_cast<const unsigned*>(a.k);
-    const unsigned* pv = static_cast<const unsigned*>(a.v);
-    const unsigned* px = static_cast<const unsigned*>(a.x);
+// Streams of one (batch, head): byte pointers at the unit's first token, uniform per workgroup.
+struct Streams {
+    const char* r;
+    const char* k;
+    const char* v;
+    const char* x;
+    long long row_bytes;       // bytes between consecutive tokens
+};
+
+// Loads tokens t0..t0+3 (t0 = chunk start + 4*group) of this thread's channel pair.
+__device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int chunk_t0, unsigned voff,
+                                          int t0, int T) {
+    const long long cb = static_cast<long long>(chunk_t0) * st.row_bytes;    // uniform
+    if (chunk_t0 + kChunk <= T) {                 // whole chunk in range: no predicates
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        const int t = t0 + s;
-        if (t < T) {
-            const long long e = (base + static_cast<long long>(t) * tok_stride) >> 1;   // dword index
-            d.r[s] = pr[e];
-            d.k[s] = pk[e];
-            d.v[s] = pv[e];
-            d.x[s] = px[e];
-        } else {                        // past the end: no key, no value, no decay (w = 1)
-            d.r[s] = 0u;
-            d.k[s] = 0u;
-            d.v[s] = 0u;
-            d.x[s] = 0xff80ff80u;       // bf16 -inf, twice
+        for (int s = 0; s < 4; ++s) {
+            const long long o = cb + s * st.row_bytes;
+            d.r[s] = *reinterpret_cast<const unsigned*>(st.r + o + voff);
+            d.k[s] = *reinterpret_cast<const unsigned*>(st.k + o + voff);
+            d.v[s] = *reinterpret_cast<const unsigned*>(st.v + o + voff);
+            d.x[s] = *reinterpret_cast<const unsigned*>(st.x + o + voff);
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (t0 + s < T) {
+                const long long o = cb + s * st.row_bytes;
+                d.r[s] = *reinterpret_cast<const unsigned*>(st.r + o + voff);
+                d.k[s] = *reinterpret_cast<const unsigned*>(st.k + o + voff);
+                d.v[s] = *reinterpret_cast<const unsigned*>(st.v + o + voff);
+                d.x[s] = *reinterpret_cast<const unsigned*>(st.x + o + voff);
+            } else {                    // past the end: no key, no value, no decay (w = 1)
+                d.r[s] = 0u;
+                d.k[s] = 0u;
+                d.v[s] = 0u;
+                d.x[s] = 0xff80ff80u;   // bf16 -inf, twice
+            }
         }
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Producer waves
+// ------------------------------------------------------------------------------------------
 template <bool kOutF32>
-__global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-
-    const int tid = threadIdx.x;
+__device__ __forceinline__ void producer(const Args& a, char* lds, int tid, int w8, int unit, int h,
+                                         long long unit_base, long long tok_stride, int nchunks) {
     const int lane = tid & 63;
-    const int wv = tid >> 6;                 // wavefront 0..3
-    // producer mapping: channel pair cp, token group tg (8 tokens)
-    const int cp = lane & 31;
-    const int hi = lane >> 5;                // which half of the chunk (tokens 0..31 / 32..63)
-    const int tg = wv + 4 * hi;
-    // MFMA mapping
+    const int cp = lane & 31;                // channel pair: channels 2cp, 2cp+1
+    const int hi = lane >> 5;                // half of the chunk (tokens 0..31 / 32..63)
+    const int tg = w8 + 8 * hi;              // 4-token group 0..15
+    const bool q4 = (w8 & 1) != 0;           // query side at level 4   (wave-uniform)
+    const bool q8 = (w8 & 2) != 0;           //                level 8
+    const bool q16 = (w8 & 4) != 0;          //                level 16; level 32's side is `hi`
     const int l16 = lane & 15;
     const int g4 = lane >> 4;
-
-    const int unit = blockIdx.x;
-    const int b = unit / a.H;
-    const int h = unit - b * a.H;
-    const long long tok_stride = static_cast<long long>(a.H) * kHeadSize;
-    const long long unit_base = static_cast<long long>(b) * a.batch_stride +
-                                static_cast<long long>(h) * kHeadSize;
-    const long long in_base = unit_base + 2 * cp;     // element offset of this thread's pair
 
     const float u0 = a.u[h * kHeadSize + 2 * cp];
     const float u1 = a.u[h * kHeadSize + 2 * cp + 1];
 
-    // state: this wave owns value columns j = 16*wv + l16; S[nb][e] = S[n = 16nb + 4g4 + e][j]
-    float4v S[4];
-    {
-        const int j = 16 * wv + l16;
-        if (a.state_in) {
-            const float* s0 = a.state_in + static_cast<long long>(unit) * 4096;
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) S[nb][e] = s0[(16 * nb + 4 * g4 + e) * 64 + j];
-        } else {
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb) S[nb] = float4v{0.f, 0.f, 0.f, 0.f};
-        }
-    }
+    Streams st;
+    st.r = static_cast<const char*>(a.r) + unit_base * 2;
+    st.k = static_cast<const char*>(a.k) + unit_base * 2;
+    st.v = static_cast<const char*>(a.v) + unit_base * 2;
+    st.x = static_cast<const char*>(a.x) + unit_base * 2;
+    st.row_bytes = tok_stride * 2;
+    const unsigned voff = static_cast<unsigned>((4 * tg * tok_stride + 2 * cp) * 2);
 
-    // score blocks above the diagonal that the A.V product still touches stay zero for good
-    {
-        // (t-block 0, i-block 1) and (t-block 2, i-block 3): 16x16 halfs each = 128 dwords
-        const int blk = tid >> 7;                    // 0 or 1
-        const int e = tid & 127;                     // dword within block: row = e>>3, col pair = e&7
+    // score blocks above the diagonal that the A.V product still touches stay zero for good:
+    // (t-block 0, i-block 1) and (t-block 2, i-block 3), 16x16 halfs each = 128 dwords
+    if (tid < 256) {
+        const int blk = tid >> 7;
+        const int e = tid & 127;
         const int row = (blk ? 32 : 0) + (e >> 3);
         const int col = (blk ? 48 : 16) + 2 * (e & 7);
-        *reinterpret_cast<unsigned*>(lds + kAT + (row * kRowHalfs + col) * 2) = 0u;
+        lds_write_u32(lds, kAT + (row * kRowHalfs + col) * 2, 0u);
     }
 
-    const int nchunks = (a.T + kChunk - 1) / kChunk;
+    // column (in halfs) of this channel pair in the permuted r*W(t,-1) tile: slot order matches
+    // the state accumulator registers that serve as the B operand of the inter-chunk read
+    const int n0 = 2 * cp;
+    const int m5 = n0 & 31;
+    const int rt_col = (n0 & 32) + 8 * ((m5 >> 2) & 3) + 4 * (m5 >> 4) + (m5 & 3);
+
     Raw cur, nxt;
-    load_chunk(cur, a, in_base, 8 * tg, a.T, tok_stride);
+    load_rows(cur, st, 0, voff, 4 * tg, a.T);
 
-    for (int c = 0; c < nchunks; ++c) {
+    for (int c = 0; c <= nchunks; ++c) {
+        const bool live = c < nchunks;
         const int c0 = c * kChunk;
-        if (c + 1 < nchunks) load_chunk(nxt, a, in_base, c0 + kChunk + 8 * tg, a.T, tok_stride);
+        float rp[2][4], ks[2][4];                    // r * prefix, k * suffix inside the group
 
-        // ---------------- producer part 1: decays and their products inside the 8-token group
-        float w[2][8], pe[2][8], se[2][8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            w[0][s] = decay_of(bf16_lo(cur.x[s]));
-            w[1][s] = decay_of(bf16_hi(cur.x[s]));
-        }
-        float gtot[2];
-#pragma unroll
-        for (int ch = 0; ch < 2; ++ch) {
-            pe[ch][0] = 1.f;
-#pragma unroll
-            for (int s = 1; s < 8; ++s) pe[ch][s] = pe[ch][s - 1] * w[ch][s - 1];
-            gtot[ch] = pe[ch][7] * w[ch][7];
-            se[ch][7] = 1.f;
-#pragma unroll
-            for (int s = 6; s >= 0; --s) se[ch][s] = se[ch][s + 1] * w[ch][s + 1];
-        }
-        *reinterpret_cast<float2*>(lds + kG + (tg * 64 + 2 * cp) * 4) = make_float2(gtot[0], gtot[1]);
-        __syncthreads();                                                        // B1
+        if (live) {
+            if (c + 1 < nchunks) load_rows(nxt, st, c0 + kChunk, voff, c0 + kChunk + 4 * tg, a.T);
 
-        // ---------------- producer part 2: group multipliers, then every operand tile
-        float m_rt[2], m_kt[2], m32[2], m16[2];
-        {
-            float2 own[4], oth[4];
+            // ---- window 1: everything that needs no other group's decays
+            float w[2][4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                own[g] = *reinterpret_cast<const float2*>(lds + kG + ((4 * hi + g) * 64 + 2 * cp) * 4);
-                oth[g] = *reinterpret_cast<const float2*>(lds + kG + ((4 * (1 - hi) + g) * 64 + 2 * cp) * 4);
+            for (int s = 0; s < 4; ++s) {
+                w[0][s] = decay_of(bf16_lo(cur.x[s]));
+                w[1][s] = decay_of(bf16_hi(cur.x[s]));
             }
+            float gtot[2];
+            half4 vt[2];
 #pragma unroll
             for (int ch = 0; ch < 2; ++ch) {
-                float o[4], q[4];
+                const float p2 = w[ch][0] * w[ch][1];            // prefix of token 2
+                const float p3 = p2 * w[ch][2];                  // prefix of token 3
+                const float s1 = w[ch][2] * w[ch][3];            // suffix of token 1
+                const float s0 = w[ch][1] * s1;                  // suffix of token 0
+                gtot[ch] = p3 * w[ch][3];
+                float r4[4], k4[4];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    o[g] = ch ? own[g].y : own[g].x;
-                    q[g] = ch ? oth[g].y : oth[g].x;
+                for (int s = 0; s < 4; ++s) {
+                    r4[s] = ch ? bf16_hi(cur.r[s]) : bf16_lo(cur.r[s]);
+                    k4[s] = ch ? bf16_hi(cur.k[s]) : bf16_lo(cur.k[s]);
+                    vt[ch][s] = static_cast<_Float16>(ch ? bf16_hi(cur.v[s]) : bf16_lo(cur.v[s]));
                 }
-                const float h_oth = (q[0] * q[1]) * (q[2] * q[3]);
-                const float h_own = (o[0] * o[1]) * (o[2] * o[3]);
-                float a_lo, a_hi, f16;      // products of the groups before / after this one in its half
-                if (wv == 0)      { a_lo = 1.f;                a_hi = o[1] * o[2] * o[3]; f16 = o[1]; }
-                else if (wv == 1) { a_lo = o[0];               a_hi = o[2] * o[3];        f16 = 1.f; }
-                else if (wv == 2) { a_lo = o[0] * o[1];        a_hi = o[3];               f16 = 1.f; }
-                else              { a_lo = o[0] * o[1] * o[2]; a_hi = 1.f;                f16 = o[2]; }
-                m_rt[ch] = hi ? h_oth * a_lo : a_lo;       // tokens before this group in the chunk
-                m_kt[ch] = hi ? a_hi : a_hi * h_oth;       // tokens after this group in the chunk
-                m32[ch] = hi ? a_lo : a_hi;
-                m16[ch] = f16;
-                if (tg == 0) *reinterpret_cast<float*>(lds + kD + (2 * cp + ch) * 4) = h_own * h_oth;
+                rp[ch][0] = r4[0];
+                rp[ch][1] = r4[1] * w[ch][0];
+                rp[ch][2] = r4[2] * p2;
+                rp[ch][3] = r4[3] * p3;
+                ks[ch][0] = k4[0] * s0;
+                ks[ch][1] = k4[1] * s1;
+                ks[ch][2] = k4[2] * w[ch][3];
+                ks[ch][3] = k4[3];
             }
-        }
-
-        const bool q16 = (wv & 2) != 0;     // query side at level 16 (wave-uniform)
-        const bool q8 = (wv & 1) != 0;      // query side at level 8  (wave-uniform)
-        // column (in halfs) of this channel pair in the permuted r*W(t,-1) tile: slot order
-        // matches the state accumulator registers used as the B operand
-        const int n0 = 2 * cp;
-        const int m5 = n0 & 31;
-        const int rt_col = (n0 & 32) + 8 * ((m5 >> 2) & 3) + 4 * (m5 >> 4) + (m5 & 3);
-
-        half8 ktv[2], vtv[2];
+            *reinterpret_cast<float2*>(lds + kG + (tg * 64 + 2 * cp) * 4) = make_float2(gtot[0], gtot[1]);
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const float r0 = bf16_lo(cur.r[s]), r1 = bf16_hi(cur.r[s]);
-            const float k0 = bf16_lo(cur.k[s]), k1 = bf16_hi(cur.k[s]);
-            const float rp0 = r0 * pe[0][s], rp1 = r1 * pe[1][s];       // r * prefix inside group
-            const float ks0 = k0 * se[0][s], ks1 = k1 * se[1][s];       // k * suffix inside group
-            const int row = 8 * tg + s;
-            const int nat = (row * kRowHalfs + 2 * cp) * 2;              // byte offset, natural order
+            for (int s = 0; s < 4; ++s) {
+                const float r0 = bf16_lo(cur.r[s]), r1 = bf16_hi(cur.r[s]);
+                const float k0 = bf16_lo(cur.k[s]), k1 = bf16_hi(cur.k[s]);
+                const int nat = ((4 * tg + s) * kRowHalfs + 2 * cp) * 2;      // natural channel order
+                // level 4: the even group of an 8-block holds keys, the odd one queries
+                lds_write_u32(lds, kZ4 + nat, q4 ? pack_h2(rp[0][s], rp[1][s]) : pack_h2(ks[0][s], ks[1][s]));
+                {   // level 2: tokens 0,1 of the group are keys, 2,3 queries
+                    float f0, f1;
+                    if (s == 0)      { f0 = k0 * w[0][1]; f1 = k1 * w[1][1]; }
+                    else if (s == 1) { f0 = k0;           f1 = k1; }
+                    else if (s == 2) { f0 = r0;           f1 = r1; }
+                    else             { f0 = r0 * w[0][2]; f1 = r1 * w[1][2]; }
+                    lds_write_u32(lds, kZ2 + nat, pack_h2(f0, f1));
+                }
+                lds_write_u32(lds, kRH + nat, pack_h2(r0, r1));      // level 1 and bonus operands
+                lds_write_u32(lds, kKH + nat, pack_h2(k0, k1));
+                lds_write_u32(lds, kRU + nat, pack_h2(r0 * u0, r1 * u1));
+            }
+#pragma unroll
+            for (int ch = 0; ch < 2; ++ch)
+                *reinterpret_cast<half4*>(lds + kVT + ((2 * cp + ch) * kRowHalfs + 4 * tg) * 2) = vt[ch];
+        }
+        __syncthreads();                                                        // barrier A
 
-            *reinterpret_cast<unsigned*>(lds + kRT + (row * kRowHalfs + rt_col) * 2) =
-                pack_h2(rp0 * m_rt[0], rp1 * m_rt[1]);
+        if (live) {
+            // ---- window 2: multipliers from the other groups' totals, then the remaining tiles
+            float m_rt[2], m_kt[2], m32[2], m16[2], m8[2];
             {
-                const float a0 = hi ? rp0 : ks0, a1 = hi ? rp1 : ks1;
-                *reinterpret_cast<unsigned*>(lds + kZ32 + nat) = pack_h2(a0 * m32[0], a1 * m32[1]);
+                float2 own[8], oth[8];
+#pragma unroll
+                for (int g = 0; g < 8; ++g) {
+                    own[g] = *reinterpret_cast<const float2*>(lds + kG + ((8 * hi + g) * 64 + 2 * cp) * 4);
+                    oth[g] = *reinterpret_cast<const float2*>(lds + kG + ((8 * (1 - hi) + g) * 64 + 2 * cp) * 4);
+                }
+#pragma unroll
+                for (int ch = 0; ch < 2; ++ch) {
+                    float o[8], q[8];
+#pragma unroll
+                    for (int g = 0; g < 8; ++g) {
+                        o[g] = ch ? own[g].y : own[g].x;
+                        q[g] = ch ? oth[g].y : oth[g].x;
+                    }
+                    const float h_oth = ((q[0] * q[1]) * (q[2] * q[3])) * ((q[4] * q[5]) * (q[6] * q[7]));
+                    // products of the groups before / after this one inside its half (w8 is uniform)
+                    float a_lo = 1.f, a_hi = 1.f, f16 = 1.f, f8 = 1.f, mine = 1.f;
+#pragma unroll
+                    for (int g = 0; g < 8; ++g) {
+                        if (g < w8) a_lo *= o[g];
+                        if (g > w8) a_hi *= o[g];
+                        if (g == w8) mine = o[g];
+                        const bool in16 = q16 ? (g >= 4 && g < w8) : (g > w8 && g < 4);
+                        if (in16) f16 *= o[g];
+                        const bool in8 = q8 ? ((w8 & 3) == 3 && g == w8 - 1) : ((w8 & 3) == 0 && g == w8 + 1);
+                        if (in8) f8 = o[g];
+                    }
+                    m_rt[ch] = hi ? h_oth * a_lo : a_lo;       // tokens before this group in the chunk
+                    m_kt[ch] = hi ? a_hi : a_hi * h_oth;       // tokens after this group in the chunk
+                    m32[ch] = hi ? a_lo : a_hi;
+                    m16[ch] = f16;
+                    m8[ch] = f8;
+                    if (tg == 0) *reinterpret_cast<float*>(lds + kD + (2 * cp + ch) * 4) = (a_lo * mine * a_hi) * h_oth;
+                }
             }
-            {
-                const float a0 = q16 ? rp0 : ks0, a1 = q16 ? rp1 : ks1;
-                *reinterpret_cast<unsigned*>(lds + kZ16 + nat) = pack_h2(a0 * m16[0], a1 * m16[1]);
+            half4 kt[2];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int row = 4 * tg + s;
+                const int nat = (row * kRowHalfs + 2 * cp) * 2;
+                lds_write_u32(lds, kRT + (row * kRowHalfs + rt_col) * 2, pack_h2(rp[0][s] * m_rt[0], rp[1][s] * m_rt[1]));
+                {
+                    const float a0 = hi ? rp[0][s] : ks[0][s], a1 = hi ? rp[1][s] : ks[1][s];
+                    lds_write_u32(lds, kZ32 + nat, pack_h2(a0 * m32[0], a1 * m32[1]));
+                }
+                {
+                    const float a0 = q16 ? rp[0][s] : ks[0][s], a1 = q16 ? rp[1][s] : ks[1][s];
+                    lds_write_u32(lds, kZ16 + nat, pack_h2(a0 * m16[0], a1 * m16[1]));
+                }
+                {
+                    const float a0 = q8 ? rp[0][s] : ks[0][s], a1 = q8 ? rp[1][s] : ks[1][s];
+                    lds_write_u32(lds, kZ8 + nat, pack_h2(a0 * m8[0], a1 * m8[1]));
+                }
+                kt[0][s] = static_cast<_Float16>(ks[0][s] * m_kt[0]);
+                kt[1][s] = static_cast<_Float16>(ks[1][s] * m_kt[1]);
             }
-            *reinterpret_cast<unsigned*>(lds + kZ8 + nat) = q8 ? pack_h2(rp0, rp1) : pack_h2(ks0, ks1);
-            {   // level 4: tokens 0..3 of the group are keys (suffix inside [0,4)), 4..7 queries
-                float f0, f1;
-                if (s == 0)      { f0 = k0 * (w[0][1] * w[0][2] * w[0][3]); f1 = k1 * (w[1][1] * w[1][2] * w[1][3]); }
-                else if (s == 1) { f0 = k0 * (w[0][2] * w[0][3]);           f1 = k1 * (w[1][2] * w[1][3]); }
-                else if (s == 2) { f0 = k0 * w[0][3];                       f1 = k1 * w[1][3]; }
-                else if (s == 3) { f0 = k0;                                 f1 = k1; }
-                else if (s == 4) { f0 = r0;                                 f1 = r1; }
-                else if (s == 5) { f0 = r0 * w[0][4];                       f1 = r1 * w[1][4]; }
-                else if (s == 6) { f0 = r0 * (w[0][4] * w[0][5]);           f1 = r1 * (w[1][4] * w[1][5]); }
-                else             { f0 = r0 * (w[0][4] * w[0][5] * w[0][6]); f1 = r1 * (w[1][4] * w[1][5] * w[1][6]); }
-                *reinterpret_cast<unsigned*>(lds + kZ4 + nat) = pack_h2(f0, f1);
-            }
-            {   // level 2: within each 4 tokens, 0,1 are keys and 2,3 queries
-                float f0, f1;
-                if ((s & 3) == 0)      { f0 = k0 * w[0][s + 1]; f1 = k1 * w[1][s + 1]; }
-                else if ((s & 3) == 1) { f0 = k0;               f1 = k1; }
-                else if ((s & 3) == 2) { f0 = r0;               f1 = r1; }
-                else                   { f0 = r0 * w[0][s - 1]; f1 = r1 * w[1][s - 1]; }
-                *reinterpret_cast<unsigned*>(lds + kZ2 + nat) = pack_h2(f0, f1);
-            }
-            *reinterpret_cast<unsigned*>(lds + kRH + nat) = pack_h2(r0, r1);
-            *reinterpret_cast<unsigned*>(lds + kKH + nat) = pack_h2(k0, k1);
-            *reinterpret_cast<unsigned*>(lds + kRU + nat) = pack_h2(r0 * u0, r1 * u1);
-
-            // transposed tiles: gather the 8 tokens of each channel
-            ktv[0][s] = static_cast<_Float16>(ks0 * m_kt[0]);
-            ktv[1][s] = static_cast<_Float16>(ks1 * m_kt[1]);
-            vtv[0][s] = static_cast<_Float16>(bf16_lo(cur.v[s]));
-            vtv[1][s] = static_cast<_Float16>(bf16_hi(cur.v[s]));
+#pragma unroll
+            for (int ch = 0; ch < 2; ++ch)
+                *reinterpret_cast<half4*>(lds + kKT + ((2 * cp + ch) * kRowHalfs + 4 * tg) * 2) = kt[ch];
         }
-#pragma unroll
-        for (int ch = 0; ch < 2; ++ch) {
-            const int off = ((2 * cp + ch) * kRowHalfs + 8 * tg) * 2;
-            *reinterpret_cast<half8*>(lds + kKT + off) = ktv[ch];
-            *reinterpret_cast<half8*>(lds + kVT + off) = vtv[ch];
-        }
-        __syncthreads();                                                        // B2
+        __syncthreads();                                                        // barrier B
 
-        // ---------------- scores: wave wv produces the columns of query block t in [16wv,16wv+16)
-        {
-            const int rowq = (16 * wv + l16) * kRowHalfs * 2 + 16 * g4;     // + 64*kk bytes
-            // diagonal block
-            float4v acc8{0.f, 0.f, 0.f, 0.f}, acc4 = acc8, acc2 = acc8, acc1 = acc8, accb = acc8;
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const half8 z8 = lds_read_h8(lds, kZ8 + rowq + 64 * kk);
-                const half8 z4 = lds_read_h8(lds, kZ4 + rowq + 64 * kk);
-                const half8 z2 = lds_read_h8(lds, kZ2 + rowq + 64 * kk);
-                const half8 rh = lds_read_h8(lds, kRH + rowq + 64 * kk);
-                const half8 kh = lds_read_h8(lds, kKH + rowq + 64 * kk);
-                const half8 ru = lds_read_h8(lds, kRU + rowq + 64 * kk);
-                acc8 = __builtin_amdgcn_mfma_f32_16x16x32_f16(z8, z8, acc8, 0, 0, 0);
-                acc4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(z4, z4, acc4, 0, 0, 0);
-                acc2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(z2, z2, acc2, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, rh, acc1, 0, 0, 0);
-                accb = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, ru, accb, 0, 0, 0);
-            }
-            float sel[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int i = 4 * g4 + e, t = l16;
-                const int d = i ^ t;
-                float val = d >= 8 ? acc8[e] : d >= 4 ? acc4[e] : d >= 2 ? acc2[e] : acc1[e];
-                val = (i == t) ? accb[e] : val;
-                sel[e] = (i > t) ? 0.f : val;
-            }
-            const int arow = (16 * wv + l16) * kRowHalfs * 2;
-            *reinterpret_cast<uint2*>(lds + kAT + arow + (16 * wv + 4 * g4) * 2) =
-                make_uint2(pack_h2(sel[0], sel[1]), pack_h2(sel[2], sel[3]));
-
-            // level 16: (t-block 1, i-block 0) and (t-block 3, i-block 2)
-            if (wv & 1) {
-                const int rowk = (16 * (wv - 1) + l16) * kRowHalfs * 2 + 16 * g4;
-                float4v acc{0.f, 0.f, 0.f, 0.f};
+        if (live) {
+            // ---- window 3: scores.  Waves 0..3: diagonal 16x16 block w8; waves 4..6: off-diagonal
+            if (w8 < 4) {
+                const int rowq = (16 * w8 + l16) * kRowHalfs * 2 + 16 * g4;     // + 64*kk bytes
+                float4v acc8{0.f, 0.f, 0.f, 0.f}, acc4 = acc8, acc2 = acc8, acc1 = acc8, accb = acc8;
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk) {
-                    const half8 zq = lds_read_h8(lds, kZ16 + rowq + 64 * kk);
-                    const half8 zk = lds_read_h8(lds, kZ16 + rowk + 64 * kk);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(zk, zq, acc, 0, 0, 0);
+                    const half8 z8 = lds_read_h8(lds, kZ8 + rowq + 64 * kk);
+                    const half8 z4 = lds_read_h8(lds, kZ4 + rowq + 64 * kk);
+                    const half8 z2 = lds_read_h8(lds, kZ2 + rowq + 64 * kk);
+                    const half8 rh = lds_read_h8(lds, kRH + rowq + 64 * kk);
+                    const half8 kh = lds_read_h8(lds, kKH + rowq + 64 * kk);
+                    const half8 ru = lds_read_h8(lds, kRU + rowq + 64 * kk);
+                    acc8 = mfma(z8, z8, acc8);
+                    acc4 = mfma(z4, z4, acc4);
+                    acc2 = mfma(z2, z2, acc2);
+                    acc1 = mfma(kh, rh, acc1);
+                    accb = mfma(kh, ru, accb);
                 }
-                *reinterpret_cast<uint2*>(lds + kAT + arow + (16 * (wv - 1) + 4 * g4) * 2) =
-                    make_uint2(pack_h2(acc[0], acc[1]), pack_h2(acc[2], acc[3]));
-            }
-            // level 32: t-blocks 2,3 against i-blocks 0,1
-            if (wv & 2) {
+                float sel[4];
 #pragma unroll
-                for (int ib = 0; ib < 2; ++ib) {
+                for (int e = 0; e < 4; ++e) {
+                    const int i = 4 * g4 + e, t = l16;
+                    const int d = i ^ t;
+                    float val = d >= 8 ? acc8[e] : d >= 4 ? acc4[e] : d >= 2 ? acc2[e] : acc1[e];
+                    val = (i == t) ? accb[e] : val;
+                    sel[e] = (i > t) ? 0.f : val;
+                }
+                *reinterpret_cast<uint2*>(lds + kAT + ((16 * w8 + l16) * kRowHalfs + 16 * w8 + 4 * g4) * 2) =
+                    make_uint2(pack_h2(sel[0], sel[1]), pack_h2(sel[2], sel[3]));
+            } else if (w8 < 7) {
+                // wave 4: level 16, blocks (t-block 1, i-block 0) and (3, 2)
+                // wave 5: level 32, blocks (2, 0) and (2, 1);  wave 6: level 32, blocks (3, 0) and (3, 1)
+                const int tile = (w8 == 4) ? kZ16 : kZ32;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int tb = (w8 == 4) ? (half ? 3 : 1) : (w8 == 5 ? 2 : 3);
+                    const int ib = (w8 == 4) ? (half ? 2 : 0) : half;
+                    const int rowq = (16 * tb + l16) * kRowHalfs * 2 + 16 * g4;
                     const int rowk = (16 * ib + l16) * kRowHalfs * 2 + 16 * g4;
                     float4v acc{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int kk = 0; kk < 2; ++kk) {
-                        const half8 zq = lds_read_h8(lds, kZ32 + rowq + 64 * kk);
-                        const half8 zk = lds_read_h8(lds, kZ32 + rowk + 64 * kk);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(zk, zq, acc, 0, 0, 0);
+                        const half8 zq = lds_read_h8(lds, tile + rowq + 64 * kk);
+                        const half8 zk = lds_read_h8(lds, tile + rowk + 64 * kk);
+                        acc = mfma(zk, zq, acc);
                     }
-                    *reinterpret_cast<uint2*>(lds + kAT + arow + (16 * ib + 4 * g4) * 2) =
+                    *reinterpret_cast<uint2*>(lds + kAT + ((16 * tb + l16) * kRowHalfs + 16 * ib + 4 * g4) * 2) =
                         make_uint2(pack_h2(acc[0], acc[1]), pack_h2(acc[2], acc[3]));
                 }
             }
         }
+        if (c > 0) {
+            // ---- the previous chunk's finished output tile: full 128-byte (bf16) rows to HBM
+            const int row = tid >> 3;
+            const int col = 8 * (tid & 7);
+            const int t = c0 - kChunk + row;
+            if (t < a.T) {
+                const long long e = unit_base + static_cast<long long>(t) * tok_stride + col;
+                if constexpr (kOutF32) {
+                    const float4* src = reinterpret_cast<const float4*>(lds + kO + (row * kORowF32 + col) * 4);
+                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(a.out) + e);
+                    const float4 q0 = src[0], q1 = src[1];
+                    dst[0] = q0;
+                    dst[1] = q1;
+                } else {
+                    const uint4 q = *reinterpret_cast<const uint4*>(lds + kO + (row * kORowBf16 + col) * 2);
+                    *reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.out) + e) = q;
+                }
+            }
+        }
+        __syncthreads();                                                        // barrier C
+        if (c + 1 < nchunks) cur = nxt;
+    }
+}
 
-        // ---------------- inter-chunk read: o[t][j] = sum_n (r_t W(t,-1))[n] S0[n][j]
+// ------------------------------------------------------------------------------------------
+// Consumer waves
+// ------------------------------------------------------------------------------------------
+template <bool kOutF32>
+__device__ __forceinline__ void consumer(const Args& a, char* lds, int lane, int cw, int unit, int nchunks) {
+    const int l16 = lane & 15;
+    const int g4 = lane >> 4;
+    const int j = 16 * cw + l16;            // value column of this lane
+
+    // S[nb][e] = state[n = 16nb + 4g4 + e][j]
+    float4v S[4];
+    if (a.state_in) {
+        const float* s0 = a.state_in + static_cast<long long>(unit) * 4096;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) S[nb][e] = s0[(16 * nb + 4 * g4 + e) * 64 + j];
+    } else {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) S[nb] = float4v{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int c = 0; c <= nchunks; ++c) {
+        const bool live = c < nchunks;
+        __syncthreads();                                                        // barrier A
+        __syncthreads();                                                        // barrier B
         float4v o[4];
-        {
+        half8 vt[2];
+        if (live) {
+            // inter-chunk read: o[t][j] = sum_n (r_t W(t,-1))[n] S0[n][j]; the state registers,
+            // rounded to fp16, are the B operand (k-slot order = the r tile's column permutation)
             half8 sh[2];
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk)
@@ -374,81 +446,75 @@ __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk) {
                     const half8 rt = lds_read_h8(lds, kRT + ((16 * tb + l16) * kRowHalfs + 32 * kk + 8 * g4) * 2);
-                    o[tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(rt, sh[kk], o[tb], 0, 0, 0);
+                    o[tb] = mfma(rt, sh[kk], o[tb]);
+                }
+            }
+            // state update: S = diag(W(64,-1)) S + (k W(64,i))^T V
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+                vt[kk] = lds_read_h8(lds, kVT + ((16 * cw + l16) * kRowHalfs + 32 * kk + 8 * g4) * 2);
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                const float4 d = *reinterpret_cast<const float4*>(lds + kD + (16 * nb + 4 * g4) * 4);
+                S[nb][0] *= d.x;
+                S[nb][1] *= d.y;
+                S[nb][2] *= d.z;
+                S[nb][3] *= d.w;
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const half8 kt = lds_read_h8(lds, kKT + ((16 * nb + l16) * kRowHalfs + 32 * kk + 8 * g4) * 2);
+                    S[nb] = mfma(kt, vt[kk], S[nb]);
                 }
             }
         }
-
-        // ---------------- state update: S = diag(W(64,-1)) S + (k W(64,i))^T V
-        half8 vt[2];
+        __syncthreads();                                                        // barrier C: scores visible
+        if (live) {
+            // intra-chunk: o += A V, then stage the tile for the producers' row stores
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-            vt[kk] = lds_read_h8(lds, kVT + ((16 * wv + l16) * kRowHalfs + 32 * kk + 8 * g4) * 2);
+            for (int tb = 0; tb < 4; ++tb) {
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-            const float4 d = *reinterpret_cast<const float4*>(lds + kD + (16 * nb + 4 * g4) * 4);
-            S[nb][0] *= d.x;
-            S[nb][1] *= d.y;
-            S[nb][2] *= d.z;
-            S[nb][3] *= d.w;
+                for (int kk = 0; kk < 2; ++kk) {
+                    if (kk == 1 && tb < 2) continue;        // keys 32..63 are never visible to t < 32
+                    const half8 at = lds_read_h8(lds, kAT + ((16 * tb + l16) * kRowHalfs + 32 * kk + 8 * g4) * 2);
+                    o[tb] = mfma(at, vt[kk], o[tb]);
+                }
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const half8 kt = lds_read_h8(lds, kKT + ((16 * nb + l16) * kRowHalfs + 32 * kk + 8 * g4) * 2);
-                S[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kt, vt[kk], S[nb], 0, 0, 0);
-            }
-        }
-        __syncthreads();                                                        // B3: scores visible
-
-        // ---------------- intra-chunk: o += A V
-#pragma unroll
-        for (int tb = 0; tb < 4; ++tb) {
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                if (kk == 1 && tb < 2) continue;            // keys 32..63 are never visible to t < 32
-                const half8 at = lds_read_h8(lds, kAT + ((16 * tb + l16) * kRowHalfs + 32 * kk + 8 * g4) * 2);
-                o[tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(at, vt[kk], o[tb], 0, 0, 0);
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                *reinterpret_cast<float*>(lds + kO + ((16 * tb + 4 * g4 + e) * kORow + 16 * wv + l16) * 4) = o[tb][e];
-        }
-        __syncthreads();                                                        // B4: output tile staged
-
-        // ---------------- coalesced store of the 64x64 output tile
-        {
-            const int row = tid >> 2;
-            const int col = 16 * (tid & 3);
-            const int t = c0 + row;
-            if (t < a.T) {
-                const float* src = reinterpret_cast<const float*>(lds + kO + (row * kORow + col) * 4);
-                const float4 q0 = *reinterpret_cast<const float4*>(src);
-                const float4 q1 = *reinterpret_cast<const float4*>(src + 4);
-                const float4 q2 = *reinterpret_cast<const float4*>(src + 8);
-                const float4 q3 = *reinterpret_cast<const float4*>(src + 12);
-                const long long e = unit_base + static_cast<long long>(t) * tok_stride + col;
-                if constexpr (kOutF32) {
-                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(a.out) + e);
-                    dst[0] = q0; dst[1] = q1; dst[2] = q2; dst[3] = q3;
-                } else {
-                    uint4* dst = reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.out) + e);
-                    dst[0] = make_uint4(pack_bf2(q0.x, q0.y), pack_bf2(q0.z, q0.w),
-                                        pack_bf2(q1.x, q1.y), pack_bf2(q1.z, q1.w));
-                    dst[1] = make_uint4(pack_bf2(q2.x, q2.y), pack_bf2(q2.z, q2.w),
-                                        pack_bf2(q3.x, q3.y), pack_bf2(q3.z, q3.w));
+                for (int e = 0; e < 4; ++e) {
+                    const int row = 16 * tb + 4 * g4 + e;
+                    if constexpr (kOutF32)
+                        *reinterpret_cast<float*>(lds + kO + (row * kORowF32 + j) * 4) = o[tb][e];
+                    else
+                        *reinterpret_cast<unsigned short*>(lds + kO + (row * kORowBf16 + j) * 2) = bf16_bits(o[tb][e]);
                 }
             }
         }
-        if (c + 1 < nchunks) cur = nxt;
     }
 
     if (a.state_out) {
-        const int j = 16 * wv + l16;
         float* so = a.state_out + static_cast<long long>(unit) * 4096;
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
             for (int e = 0; e < 4; ++e) so[(16 * nb + 4 * g4 + e) * 64 + j] = S[nb][e];
     }
+}
+
+template <bool kOutF32>
+__global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int tid = threadIdx.x;
+    const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int unit = blockIdx.x;
+    const int b = unit / a.H;
+    const int h = unit - b * a.H;
+    const long long tok_stride = static_cast<long long>(a.H) * kHeadSize;
+    const long long unit_base = static_cast<long long>(b) * a.batch_stride +
+                                static_cast<long long>(h) * kHeadSize;
+    const int nchunks = (a.T + kChunk - 1) / kChunk;
+    if (wid < kProducerWaves)
+        producer<kOutF32>(a, lds, tid, wid, unit, h, unit_base, tok_stride, nchunks);
+    else
+        consumer<kOutF32>(a, lds, tid & 63, wid - kProducerWaves, unit, nchunks);
 }
 
 }  // namespace
