@@ -108,44 +108,42 @@ struct Raw {           // one chunk's inputs of a producer thread: 4 tokens x on
     unsigned r[4], k[4], v[4], x[4];
 };
 
-// Streams of one (batch, head): byte pointers at the unit's first token, uniform per workgroup.
+// The four input streams of one (batch, head) are read through raw buffer descriptors whose
+// base is the chunk's first token row (uniform, rebuilt per chunk with scalar adds) and whose
+// extent ends with the unit's last token, so rows past the end of the sequence read as zero
+// without predicates.  Row offsets of a thread's 4 tokens are kernel-lifetime constants.
 struct Streams {
     const char* r;
     const char* k;
     const char* v;
     const char* x;
     long long row_bytes;       // bytes between consecutive tokens
+    long long span_bytes;      // bytes from the unit's first token row to the end of its last one
 };
 
-// Loads tokens t0..t0+3 (t0 = chunk start + 4*group) of this thread's channel pair.
-__device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int chunk_t0, unsigned voff,
-                                          int t0, int T) {
-    const long long cb = static_cast<long long>(chunk_t0) * st.row_bytes;    // uniform
-    if (chunk_t0 + kChunk <= T) {                 // whole chunk in range: no predicates
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const char* base, long long chunk_off,
+                                                           long long span_bytes) {
+    long long left = span_bytes - chunk_off;
+    if (left < 0) left = 0;
+    if (left > 0x7fffffffLL) left = 0x7fffffffLL;
+    // raw buffer (stride 0), 32-bit data format
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base + chunk_off), 0,
+                                             static_cast<int>(left), 0x00020000);
+}
+
+// Loads the thread's 4 tokens x channel pair of the chunk starting at token chunk_t0.
+__device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int chunk_t0, const int (&voff)[4]) {
+    const long long off = static_cast<long long>(chunk_t0) * st.row_bytes;       // uniform
+    const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r, off, st.span_bytes);
+    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(st.k, off, st.span_bytes);
+    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(st.v, off, st.span_bytes);
+    const __amdgpu_buffer_rsrc_t rx = chunk_rsrc(st.x, off, st.span_bytes);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const long long o = cb + s * st.row_bytes;
-            d.r[s] = *reinterpret_cast<const unsigned*>(st.r + o + voff);
-            d.k[s] = *reinterpret_cast<const unsigned*>(st.k + o + voff);
-            d.v[s] = *reinterpret_cast<const unsigned*>(st.v + o + voff);
-            d.x[s] = *reinterpret_cast<const unsigned*>(st.x + o + voff);
-        }
-    } else {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            if (t0 + s < T) {
-                const long long o = cb + s * st.row_bytes;
-                d.r[s] = *reinterpret_cast<const unsigned*>(st.r + o + voff);
-                d.k[s] = *reinterpret_cast<const unsigned*>(st.k + o + voff);
-                d.v[s] = *reinterpret_cast<const unsigned*>(st.v + o + voff);
-                d.x[s] = *reinterpret_cast<const unsigned*>(st.x + o + voff);
-            } else {                    // past the end: no key, no value, no decay (w = 1)
-                d.r[s] = 0u;
-                d.k[s] = 0u;
-                d.v[s] = 0u;
-                d.x[s] = 0xff80ff80u;   // bf16 -inf, twice
-            }
-        }
+    for (int s = 0; s < 4; ++s) {
+        d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, 0);
+        d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, 0);
+        d.k[s] = __builtin_amdgcn_raw_buffer_load_b32(rk, voff[s], 0, 0);
+        d.v[s] = __builtin_amdgcn_raw_buffer_load_b32(rv, voff[s], 0, 0);
     }
 }
 
@@ -174,7 +172,11 @@ __device__ __forceinline__ void producer(const Args& a, char* lds, int tid, int 
     st.v = static_cast<const char*>(a.v) + unit_base * 2;
     st.x = static_cast<const char*>(a.x) + unit_base * 2;
     st.row_bytes = tok_stride * 2;
-    const unsigned voff = static_cast<unsigned>((4 * tg * tok_stride + 2 * cp) * 2);
+    st.span_bytes = static_cast<long long>(a.T - 1) * st.row_bytes + kHeadSize * 2;
+    int voff[4];                                   // byte offsets of this thread's 4 token rows
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        voff[s] = static_cast<int>((4 * tg + s) * st.row_bytes + 4 * cp);
 
     // score blocks above the diagonal that the A.V product still touches stay zero for good:
     // (t-block 0, i-block 1) and (t-block 2, i-block 3), 16x16 halfs each = 128 dwords
@@ -192,8 +194,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds, int tid, int 
     const int m5 = n0 & 31;
     const int rt_col = (n0 & 32) + 8 * ((m5 >> 2) & 3) + 4 * (m5 >> 4) + (m5 & 3);
 
-    Raw cur, nxt;
-    load_rows(cur, st, 0, voff, 4 * tg, a.T);
+    Raw cur;
+    load_rows(cur, st, 0, voff);
 
     for (int c = 0; c <= nchunks; ++c) {
         const bool live = c < nchunks;
@@ -201,8 +203,12 @@ __device__ __forceinline__ void producer(const Args& a, char* lds, int tid, int 
         float rp[2][4], ks[2][4];                    // r * prefix, k * suffix inside the group
 
         if (live) {
-            if (c + 1 < nchunks) load_rows(nxt, st, c0 + kChunk, voff, c0 + kChunk + 4 * tg, a.T);
-
+            if (c0 + kChunk > a.T) {
+                // last, partial chunk: tokens past the end were read as zeros; give them w = 1
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    if (c0 + 4 * tg + s >= a.T) cur.x[s] = 0xff80ff80u;      // bf16 -inf, twice
+            }
             // ---- window 1: everything that needs no other group's decays
             float w[2][4];
 #pragma unroll
@@ -258,6 +264,9 @@ __device__ __forceinline__ void producer(const Args& a, char* lds, int tid, int 
 #pragma unroll
             for (int ch = 0; ch < 2; ++ch)
                 *reinterpret_cast<half4*>(lds + kVT + ((2 * cp + ch) * kRowHalfs + 4 * tg) * 2) = vt[ch];
+            // this chunk's raw inputs are consumed: fetch the next chunk into the same registers;
+            // the loads stay in flight through windows 2 and 3
+            if (c + 1 < nchunks) load_rows(cur, st, c0 + kChunk, voff);
         }
         __syncthreads();                                                        // barrier A
 
@@ -280,18 +289,30 @@ __device__ __forceinline__ void producer(const Args& a, char* lds, int tid, int 
                         q[g] = ch ? oth[g].y : oth[g].x;
                     }
                     const float h_oth = ((q[0] * q[1]) * (q[2] * q[3])) * ((q[4] * q[5]) * (q[6] * q[7]));
-                    // products of the groups before / after this one inside its half (w8 is uniform)
-                    float a_lo = 1.f, a_hi = 1.f, f16 = 1.f, f8 = 1.f, mine = 1.f;
-#pragma unroll
-                    for (int g = 0; g < 8; ++g) {
-                        if (g < w8) a_lo *= o[g];
-                        if (g > w8) a_hi *= o[g];
-                        if (g == w8) mine = o[g];
-                        const bool in16 = q16 ? (g >= 4 && g < w8) : (g > w8 && g < 4);
-                        if (in16) f16 *= o[g];
-                        const bool in8 = q8 ? ((w8 & 3) == 3 && g == w8 - 1) : ((w8 & 3) == 0 && g == w8 + 1);
-                        if (in8) f8 = o[g];
+                    // products of the groups before (a_lo) / after (a_hi) this one inside its half,
+                    // and the level-16 / level-8 multipliers; w8 is wave-uniform
+                    float a_lo, a_hi, f16, f8;
+                    switch (w8) {
+                        case 0:  f8 = o[1]; f16 = o[1] * (o[2] * o[3]); a_lo = 1.f;
+                                 a_hi = f16 * ((o[4] * o[5]) * (o[6] * o[7])); break;
+                        case 1:  f8 = 1.f; f16 = o[2] * o[3]; a_lo = o[0];
+                                 a_hi = f16 * ((o[4] * o[5]) * (o[6] * o[7])); break;
+                        case 2:  f8 = 1.f; f16 = o[3]; a_lo = o[0] * o[1];
+                                 a_hi = f16 * ((o[4] * o[5]) * (o[6] * o[7])); break;
+                        case 3:  f8 = o[2]; f16 = 1.f; a_lo = (o[0] * o[1]) * o[2];
+                                 a_hi = (o[4] * o[5]) * (o[6] * o[7]); break;
+                        case 4:  f8 = o[5]; f16 = 1.f; a_lo = (o[0] * o[1]) * (o[2] * o[3]);
+                                 a_hi = o[5] * (o[6] * o[7]); break;
+                        case 5:  f8 = 1.f; f16 = o[4]; a_lo = ((o[0] * o[1]) * (o[2] * o[3])) * o[4];
+                                 a_hi = o[6] * o[7]; break;
+                        case 6:  f8 = 1.f; f16 = o[4] * o[5]; a_lo = ((o[0] * o[1]) * (o[2] * o[3])) * f16;
+                                 a_hi = o[7]; break;
+                        default: f8 = o[6]; f16 = (o[4] * o[5]) * o[6]; a_lo = ((o[0] * o[1]) * (o[2] * o[3])) * f16;
+                                 a_hi = 1.f; break;
                     }
+                    float mine = o[0];
+#pragma unroll
+                    for (int g = 1; g < 8; ++g) mine = (g == w8) ? o[g] : mine;
                     m_rt[ch] = hi ? h_oth * a_lo : a_lo;       // tokens before this group in the chunk
                     m_kt[ch] = hi ? a_hi : a_hi * h_oth;       // tokens after this group in the chunk
                     m32[ch] = hi ? a_lo : a_hi;
@@ -399,7 +420,6 @@ __device__ __forceinline__ void producer(const Args& a, char* lds, int tid, int 
             }
         }
         __syncthreads();                                                        // barrier C
-        if (c + 1 < nchunks) cur = nxt;
     }
 }
 
