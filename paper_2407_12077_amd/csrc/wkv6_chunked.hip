@@ -431,6 +431,8 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds, int lane, int
     const int l16 = lane & 15;
     const int g4 = lane >> 4;
     const int j = 16 * cw + l16;            // value column of this lane
+    // the consumers carry the only sequential chain: let the SIMD arbiter prefer them
+    __builtin_amdgcn_s_setprio(3);
 
     // S[nb][e] = state[n = 16nb + 4g4 + e][j]
     float4v S[4];
