@@ -23,7 +23,10 @@ MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 MFMA
 
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each
 # scaled by the same counter's reading for a plain copy kernel); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # FETCH_SIZE 262 330 KiB x 2.0 (copy calibration) + WRITE_SIZE 135 168 KiB x 1.0
+    "config2:wkv6_prefill_bf16": int(262330 * 1024 * 2.0 + 135168 * 1024 * 1.0),
+}
 
 
 def algorithmic_bytes(cfg, out_bytes, state_in, state_out=True):
