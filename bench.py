@@ -65,7 +65,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--entry", default="wkv6_prefill_bf16",
-                    choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent"])
+                    choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent",
+                             "wkv6_prefill_bf16_split"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 512 MiB device copy (calibrates rocprofv3 byte counters)")
@@ -91,15 +92,26 @@ def main():
     r, k, v, x = (dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "x"))
     u = dev(inp["u"], torch.float32)
     s_in = dev(inp["state_in"], torch.float32)
-    out_f32 = args.entry != "wkv6_prefill_bf16"
+    out_f32 = args.entry not in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_split")
     out = torch.empty((B, T, H, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
     s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
     fn = getattr(wkv, args.entry)
 
     stream = torch.cuda.current_stream()         # the stream the kernels are launched on
 
-    def step():
-        fn(B, T, H, N, r, k, v, x, u, s_in, out, s_out, stream.cuda_stream)
+    if args.entry == "wkv6_prefill_bf16_split":
+        segments = wkv.wkv6_split_segments(B, T, H, N)
+        ws_bytes = wkv.wkv6_split_workspace_bytes(B, T, H, N, segments)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")   # caller-owned workspace
+
+        def step():
+            fn(B, T, H, N, r, k, v, x, u, s_in, out, s_out, wkv.WKV6_DTYPE_BF16, segments, ws, ws_bytes,
+               stream.cuda_stream)
+    else:
+        segments = 1
+
+        def step():
+            fn(B, T, H, N, r, k, v, x, u, s_in, out, s_out, stream.cuda_stream)
 
     if args.copy_probe:
         src = torch.empty(256 * 1024 * 1024, dtype=torch.bfloat16, device="cuda").fill_(1.0)
@@ -143,7 +155,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index} ({cfg.name}): B={B} T={T} H={H} N={N}, "
                                f"{'nonzero' if s_in is not None else 'zero'} initial state",
-                   "entry": args.entry, "global_batch": B, "seq_len": T},
+                   "entry": args.entry, "segments": segments, "global_batch": B, "seq_len": T},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(key),
                      "kernel_ms_avg": kernel_ms, "kernel_ms_min": min(per_launch_ms),

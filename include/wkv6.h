@@ -92,6 +92,31 @@ int wkv6_prefill_bf16_strided(int B, int T, int H, int N,
                               void *out, float *state_out,
                               long long batch_stride, int out_dtype, void *stream);
 
+/*
+ * Token-split variant for few (batch, head) units and long sequences (B*H well below the 256
+ * compute units, e.g. one long context): the T axis is cut into `segments` pieces that run in
+ * parallel.  Three passes are enqueued on `stream`: (1) every segment's local state and total
+ * decay from a zero state, using k, v, x only; (2) a sequential fold over segments that turns
+ * them into the state entering each segment (the recurrence is linear in the state: S_out =
+ * diag(prod w) S_in + S_local); (3) the full computation of every segment from that state.
+ * Results equal the single-pass entry points up to rounding order.  `workspace` is caller-owned
+ * device memory of at least wkv6_split_workspace_bytes() bytes, 16-byte aligned, used only
+ * during the call's kernels; calls sharing a workspace must be ordered on one stream.
+ * segments == 1 (or T too short to split) runs the single-pass kernel and ignores workspace.
+ * out_dtype is a wkv6_dtype.
+ */
+int wkv6_prefill_bf16_split(int B, int T, int H, int N,
+                            const void *r, const void *k, const void *v, const void *x,
+                            const float *u, const float *state_in,
+                            void *out, float *state_out, int out_dtype, int segments,
+                            void *workspace, long long workspace_bytes, void *stream);
+
+/* Bytes of workspace wkv6_prefill_bf16_split needs for this shape (-1 for invalid arguments). */
+long long wkv6_split_workspace_bytes(int B, int T, int H, int N, int segments);
+
+/* Segment count this library would pick for the shape on a 256-CU MI355X (1 = do not split). */
+int wkv6_split_segments(int B, int T, int H, int N);
+
 /* All-fp32 tensors.  Token-by-token kernel with the state in fp32 registers. */
 int wkv6_prefill_f32(int B, int T, int H, int N,
                      const float *r, const float *k, const float *v, const float *x,

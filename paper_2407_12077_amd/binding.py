@@ -16,7 +16,8 @@ WKV6_DTYPE_BF16 = 0
 WKV6_DTYPE_F32 = 1
 
 EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_strided",
-           "wkv6_prefill_f32", "wkv6_prefill_bf16_recurrent", "wkv6_status_string",
+           "wkv6_prefill_f32", "wkv6_prefill_bf16_recurrent", "wkv6_prefill_bf16_split",
+           "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_status_string",
            "wkv6_version")
 
 _lib = None
@@ -45,6 +46,12 @@ def load():
             fn.argtypes = common + [vp]
         lib.wkv6_prefill_bf16_strided.restype = i
         lib.wkv6_prefill_bf16_strided.argtypes = common + [ll, i, vp]
+        lib.wkv6_prefill_bf16_split.restype = i
+        lib.wkv6_prefill_bf16_split.argtypes = common + [i, i, vp, ll, vp]
+        lib.wkv6_split_workspace_bytes.restype = ll
+        lib.wkv6_split_workspace_bytes.argtypes = [i, i, i, i, i]
+        lib.wkv6_split_segments.restype = i
+        lib.wkv6_split_segments.argtypes = [i, i, i, i]
         lib.wkv6_status_string.restype = ctypes.c_char_p
         lib.wkv6_status_string.argtypes = [i]
         lib.wkv6_version.restype = i
@@ -91,6 +98,20 @@ def wkv6_prefill_bf16_strided(B, T, H, N, r, k, v, x, u, state_in, out, state_ou
                               batch_stride, out_dtype, stream=None):
     _call("wkv6_prefill_bf16_strided", B, T, H, N, r, k, v, x, u, state_in, out, state_out,
           stream, ctypes.c_longlong(batch_stride), int(out_dtype))
+
+
+def wkv6_prefill_bf16_split(B, T, H, N, r, k, v, x, u, state_in, out, state_out, out_dtype,
+                            segments, workspace, workspace_bytes, stream=None):
+    _call("wkv6_prefill_bf16_split", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream,
+          int(out_dtype), int(segments), _ptr(workspace), ctypes.c_longlong(workspace_bytes))
+
+
+def wkv6_split_workspace_bytes(B, T, H, N, segments):
+    return load().wkv6_split_workspace_bytes(B, T, H, N, segments)
+
+
+def wkv6_split_segments(B, T, H, N):
+    return load().wkv6_split_segments(B, T, H, N)
 
 
 def wkv6_prefill_f32(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):

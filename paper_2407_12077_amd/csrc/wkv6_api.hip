@@ -34,6 +34,7 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     a.r = r; a.k = k; a.v = v; a.x = x; a.u = u;
     a.state_in = state_in; a.out = out; a.state_out = state_out;
     a.batch_stride = batch_stride;
+    a.segs = 1; a.T_last = T; a.seg_stride = 0; a.decay_out = nullptr;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;
@@ -42,7 +43,7 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     else if (path == Path::kRecurrent)
         err = wkv6::launch_recurrent(a, in_bf16, s);
     else
-        err = wkv6::launch_chunked(a, out_f32, s);
+        err = wkv6::launch_chunked(a, out_f32 ? wkv6::ChunkedMode::kF32Out : wkv6::ChunkedMode::kBf16Out, s);
     return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
 }
 
@@ -101,5 +102,94 @@ const char* wkv6_status_string(int status) {
 }
 
 int wkv6_version(void) { return 100; }
+
+}  // extern "C"
+
+// ---- token-split variant: three enqueued passes over caller-provided workspace
+
+namespace {
+
+struct SplitPlan {
+    int segs;        // segments actually used
+    int seg_len;     // tokens per segment (multiple of 32), last one shorter
+    int last_len;
+};
+
+SplitPlan plan_split(int T, int segments) {
+    SplitPlan p;
+    if (segments < 1) segments = 1;
+    long long len = (static_cast<long long>(T) + segments - 1) / segments;
+    len = (len + 31) / 32 * 32;
+    if (len < 32) len = 32;
+    p.seg_len = static_cast<int>(len);
+    p.segs = static_cast<int>((T + len - 1) / len);
+    if (p.segs < 1) p.segs = 1;
+    p.last_len = T - (p.segs - 1) * p.seg_len;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wkv6_split_segments(int B, int T, int H, int N) {
+    if (N != wkv6::kHeadSize || B < 1 || T < 1 || H < 1) return 1;
+    const long long units = static_cast<long long>(B) * H;
+    const int cus = 256;                         // workgroups resident at once (one per CU)
+    if (units * 4 > cus * 3) return 1;           // already fills three quarters of the chip
+    long long segs = cus / units;
+    const long long by_len = T / 2048;           // keep segments long enough to amortise pass 1
+    if (segs > by_len) segs = by_len;
+    return segs < 2 ? 1 : static_cast<int>(segs);
+}
+
+long long wkv6_split_workspace_bytes(int B, int T, int H, int N, int segments) {
+    if (N != wkv6::kHeadSize || B < 0 || T < 0 || H < 1 || segments < 1) return -1;
+    const SplitPlan p = plan_split(T > 0 ? T : 1, segments);
+    return static_cast<long long>(B) * p.segs * H * (wkv6::kHeadSize * wkv6::kHeadSize + wkv6::kHeadSize) * 4;
+}
+
+int wkv6_prefill_bf16_split(int B, int T, int H, int N, const void* r, const void* k, const void* v,
+                            const void* x, const float* u, const float* state_in, void* out,
+                            float* state_out, int out_dtype, int segments, void* workspace,
+                            long long workspace_bytes, void* stream) {
+    if (out_dtype != WKV6_DTYPE_BF16 && out_dtype != WKV6_DTYPE_F32) return WKV6_ERR_UNSUPPORTED;
+    if (N != wkv6::kHeadSize) return WKV6_ERR_UNSUPPORTED;
+    if (B < 0 || T < 0 || H < 1 || H > 262144 || segments < 1) return WKV6_ERR_SHAPE;
+    const SplitPlan p = plan_split(T > 0 ? T : 1, segments);
+    if (T == 0 || B == 0 || p.segs == 1)
+        return run(B, T, H, N, r, k, v, x, u, state_in, out, state_out,
+                   static_cast<long long>(T) * H * N, true, out_dtype == WKV6_DTYPE_F32,
+                   Path::kChunked, stream);
+    if (!u || !r || !k || !v || !x || !out || !workspace) return WKV6_ERR_NULL;
+    if (misaligned(r) || misaligned(k) || misaligned(v) || misaligned(x) || misaligned(out) ||
+        misaligned(u) || misaligned(state_in) || misaligned(state_out) || misaligned(workspace))
+        return WKV6_ERR_ALIGN;
+    if (workspace_bytes < wkv6_split_workspace_bytes(B, T, H, N, segments)) return WKV6_ERR_SHAPE;
+    if (static_cast<long long>(B) * p.segs * H > 0x7fffffffLL) return WKV6_ERR_SHAPE;
+
+    float* seg_state = static_cast<float*>(workspace);
+    float* seg_decay = seg_state + static_cast<long long>(B) * p.segs * H * 4096;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    wkv6::Args a;
+    a.B = B; a.T = p.seg_len; a.H = H;
+    a.r = r; a.k = k; a.v = v; a.x = x; a.u = u;
+    a.batch_stride = static_cast<long long>(T) * H * N;
+    a.segs = p.segs; a.T_last = p.last_len;
+    a.seg_stride = static_cast<long long>(p.seg_len) * H * N;
+    // pass 1: every segment from a zero state, no output: its local state and total decay
+    a.state_in = nullptr; a.out = nullptr; a.state_out = seg_state; a.decay_out = seg_decay;
+    if (wkv6::launch_chunked(a, wkv6::ChunkedMode::kStateOnly, s) != hipSuccess) return WKV6_ERR_LAUNCH;
+    // pass 2: the state entering every segment (in place) and the final state
+    if (wkv6::launch_combine_segments(B, H, p.segs, state_in, seg_state, seg_decay, state_out, s) != hipSuccess)
+        return WKV6_ERR_LAUNCH;
+    // pass 3: the full computation of every segment from its true entering state
+    a.state_in = seg_state; a.out = out; a.state_out = nullptr; a.decay_out = nullptr;
+    const wkv6::ChunkedMode mode = out_dtype == WKV6_DTYPE_F32 ? wkv6::ChunkedMode::kF32Out
+                                                               : wkv6::ChunkedMode::kBf16Out;
+    if (wkv6::launch_chunked(a, mode, s) != hipSuccess) return WKV6_ERR_LAUNCH;
+    return WKV6_OK;
+}
 
 }  // extern "C"

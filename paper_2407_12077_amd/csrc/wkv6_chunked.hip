@@ -152,6 +152,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const char* base, l
                                              static_cast<int>(left), 0x00020000);
 }
 
+template <bool kSkipR>
 __device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int t0, const int (&voff)[4]) {
     const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
     const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r, off, st.span_bytes);
@@ -161,7 +162,8 @@ __device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int t0, con
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, 0);
-        d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, 0);
+        if constexpr (!kSkipR) d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, 0);
+        else d.r[s] = 0u;
         d.k[s] = __builtin_amdgcn_raw_buffer_load_b32(rk, voff[s], 0, 0);
         d.v[s] = __builtin_amdgcn_raw_buffer_load_b32(rv, voff[s], 0, 0);
     }
@@ -178,9 +180,11 @@ struct Prep {
 // ------------------------------------------------------------------------------------------
 // Producer waves: group pg (0/1) = chunk parity, wq = wave inside the group
 // ------------------------------------------------------------------------------------------
-template <bool kOutF32>
+template <int kMode>
 __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, int pg, int wq, int h,
-                                         long long unit_base, long long tok_stride, int nchunks) {
+                                         long long unit_base, long long tok_stride, int T, int nchunks) {
+    constexpr bool kOutF32 = kMode == 1;
+    constexpr bool kStateOnly = kMode == 2;
     char* lds = lds_all + pg * kBuf;         // this group's tiles
     const int lane = tid & 63;
     const int gtid = tid & 255;              // thread inside the group
@@ -202,7 +206,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     st.v = static_cast<const char*>(a.v) + unit_base * 2;
     st.x = static_cast<const char*>(a.x) + unit_base * 2;
     st.row_bytes = tok_stride * 2;
-    st.span_bytes = static_cast<long long>(a.T - 1) * st.row_bytes + kHeadSize * 2;
+    st.span_bytes = static_cast<long long>(T - 1) * st.row_bytes + kHeadSize * 2;
     int voff[4];                                   // byte offsets of this thread's 4 token rows
 #pragma unroll
     for (int s = 0; s < 4; ++s)
@@ -210,7 +214,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 
     // the score block above the diagonal that the A.V product still touches, (t-block 0,
     // i-block 1), stays zero for good in both partial score tiles: 2 x 16x16 halfs = 256 dwords
-    {
+    if constexpr (!kStateOnly) {
         const int which = gtid >> 7;                 // A0 / A1
         const int e = gtid & 127;                    // row = e>>3, column pair = e&7
         lds_write_u32(lds, (which ? kA1 : kA0) + (e >> 3) * kRow + (16 + 2 * (e & 7)) * 2, 0u);
@@ -229,11 +233,11 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // the thread's 4-token group (published in G), and every operand that needs nothing else.
     auto digest = [&](int c, Raw& cur) {
         const int t0 = c * kChunk;
-        if (t0 + kChunk > a.T) {
+        if (t0 + kChunk > T) {
             // last, partial chunk: tokens past the end were read as zeros; give them w = 1
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                if (t0 + 4 * g8 + s >= a.T) cur.x[s] = 0xff80ff80u;      // bf16 -inf, twice
+                if (t0 + 4 * g8 + s >= T) cur.x[s] = 0xff80ff80u;      // bf16 -inf, twice
         }
         float w[2][4];
 #pragma unroll
@@ -317,6 +321,11 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         for (int s = 0; s < 4; ++s) {
             const int row = (4 * g8 + s) * kRow;
             const int nat = row + 4 * cp;                    // natural channel order
+            if constexpr (kStateOnly) {
+                lds_write_u32(lds, kVT + nat, pr.vt[s]);
+                lds_write_u32(lds, kKT + nat, pack_h2(pr.ks[0][s] * m_kt[0], pr.ks[1][s] * m_kt[1]));
+                continue;
+            }
             // level 4: the even group of an 8-block holds keys, the odd one queries
             lds_write_u32(lds, kZ4 + nat, q4 ? pack_h2(pr.rp[0][s], pr.rp[1][s]) : pack_h2(pr.ks[0][s], pr.ks[1][s]));
             lds_write_u32(lds, kZ2 + nat, pr.z2[s]);
@@ -385,7 +394,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         const int row = gtid >> 3;
         const int col = 8 * (gtid & 7);
         const int t = c * kChunk + row;
-        if (t < a.T) {
+        if (t < T) {
             const long long e = unit_base + static_cast<long long>(t) * tok_stride + col;
             if constexpr (kOutF32) {
                 const float4* src = reinterpret_cast<const float4*>(lds + kO + (row * kORowF32 + col) * 4);
@@ -406,14 +415,16 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // pipeline is full.
     auto phase_t = [&](int c, Raw& mine) {
         if (c < nchunks) write_tiles();
-        if (c + 4 < nchunks) load_rows(mine, st, (c + 4) * kChunk, voff);
+        if (c + 4 < nchunks) load_rows<kStateOnly>(mine, st, (c + 4) * kChunk, voff);
     };
     // Phase S of chunk c: scores, decays of this group's next chunk (c+2, raw registers `next`),
     // then the finished rows of chunk c-2 (last: nothing here waits for the stores' acknowledgement).
     auto phase_s = [&](int c, Raw& next) {
-        if (c >= 0 && c < nchunks) scores();
+        if constexpr (!kStateOnly)
+            if (c >= 0 && c < nchunks) scores();
         if (c + 2 < nchunks) digest(c + 2, next);
-        if (c >= 2 && c - 2 < nchunks) store_rows(c - 2);
+        if constexpr (!kStateOnly)
+            if (c >= 2 && c - 2 < nchunks) store_rows(c - 2);
     };
 
     // Windows 0 .. nwin-1 (nwin a multiple of 4); group 0 runs T in even windows and S in odd
@@ -422,8 +433,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // of the group, which the loops spell out by handling two of them per iteration.
     const int nwin = (nchunks + 6) & ~3;
     if (pg == 0) {
-        load_rows(raw_a, st, 0, voff);
-        if (2 < nchunks) load_rows(raw_b, st, 2 * kChunk, voff);
+        load_rows<kStateOnly>(raw_a, st, 0, voff);
+        if (2 < nchunks) load_rows<kStateOnly>(raw_b, st, 2 * kChunk, voff);
         digest(0, raw_a);
         __syncthreads();                                                        // start barrier
 #pragma clang loop unroll(disable)
@@ -438,8 +449,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             __syncthreads();                                                    // window barrier
         }
     } else {
-        if (1 < nchunks) load_rows(raw_a, st, kChunk, voff);
-        if (3 < nchunks) load_rows(raw_b, st, 3 * kChunk, voff);
+        if (1 < nchunks) load_rows<kStateOnly>(raw_a, st, kChunk, voff);
+        if (3 < nchunks) load_rows<kStateOnly>(raw_b, st, 3 * kChunk, voff);
         __syncthreads();                                                        // start barrier
         phase_s(-1, raw_a);                      // window 0: only the digest of chunk 1 applies
         __syncthreads();                                                        // window barrier
@@ -468,8 +479,10 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 // ------------------------------------------------------------------------------------------
 // Consumer waves
 // ------------------------------------------------------------------------------------------
-template <bool kOutF32>
+template <int kMode>
 __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane, int cw, int unit, int nchunks) {
+    constexpr bool kOutF32 = kMode == 1;
+    constexpr bool kStateOnly = kMode == 2;
     const int l16 = lane & 15;
     const int g4 = lane >> 4;
     const int j = 16 * cw + l16;            // value column of this lane
@@ -489,6 +502,7 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
         for (int nb = 0; nb < 4; ++nb) S[nb] = float4v{0.f, 0.f, 0.f, 0.f};
     }
 
+    float dtot = 1.f;   // product of all decays so far, key channel `lane` (only with decay_out)
     float4v o[2];       // output rows of the chunk whose state chain ran last: 2 t-blocks x 4 rows
     half8 vt;           // its V operand: 32 tokens x this lane's column
     // byte offset of this lane's share of a transposing read: token row (8*g4 + (l16>>2)),
@@ -499,7 +513,7 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
     const int nwin = (nchunks + 6) & ~3;
 #pragma clang loop unroll(disable)
     for (int n = 0; n < nwin; ++n) {
-        if (n >= 2 && n - 2 < nchunks) {
+        if (!kStateOnly && n >= 2 && n - 2 < nchunks) {
             // chunk n-2: o += A V (two partial score tiles), then stage for the producers' stores
             char* lds = lds_all + (n & 1) * kBuf;
 #pragma unroll
@@ -524,21 +538,24 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
             const char* lds = lds_all + ((n - 1) & 1) * kBuf;
             // inter-chunk read: o[t][j] = sum_n (r_t W(t,-1))[n] S[n][j]; the state registers,
             // rounded to fp16, are the B operand (k-slot order = the r tile's column permutation)
-            half8 sh[2];
+            if constexpr (!kStateOnly) {
+                half8 sh[2];
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
+                for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    sh[kk][e] = static_cast<_Float16>(S[2 * kk + (e >> 2)][e & 3]);
+                    for (int e = 0; e < 8; ++e)
+                        sh[kk][e] = static_cast<_Float16>(S[2 * kk + (e >> 2)][e & 3]);
 #pragma unroll
-            for (int tq = 0; tq < 2; ++tq) {
-                o[tq] = float4v{0.f, 0.f, 0.f, 0.f};
+                for (int tq = 0; tq < 2; ++tq) {
+                    o[tq] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const half8 rt = lds_read_h8(lds, kRT + (16 * tq + l16) * kRow + (32 * kk + 8 * g4) * 2);
-                    o[tq] = mfma(rt, sh[kk], o[tq]);
+                    for (int kk = 0; kk < 2; ++kk) {
+                        const half8 rt = lds_read_h8(lds, kRT + (16 * tq + l16) * kRow + (32 * kk + 8 * g4) * 2);
+                        o[tq] = mfma(rt, sh[kk], o[tq]);
+                    }
                 }
             }
+            if (a.decay_out) dtot *= *reinterpret_cast<const float*>(lds + kD + lane * 4);
             // state update: S = diag(W(32,-1)) S + (k W(32,i))^T V over the chunk's 32 tokens
             vt = lds_read_tr8(lds, kVT + tr_lane + 32 * cw);
 #pragma unroll
@@ -562,42 +579,92 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
 #pragma unroll
             for (int e = 0; e < 4; ++e) so[(16 * nb + 4 * g4 + e) * 64 + j] = S[nb][e];
     }
+    if (a.decay_out && cw == 0) a.decay_out[static_cast<long long>(unit) * kHeadSize + lane] = dtot;
 }
 
-template <bool kOutF32>
+template <int kMode>
 __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
     const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int unit = blockIdx.x;
-    const int b = unit / a.H;
-    const int h = unit - b * a.H;
+    const int unit = blockIdx.x;                 // (batch * segs + segment) * H + head
+    const int bs = unit / a.H;
+    const int h = unit - bs * a.H;
+    const int b = bs / a.segs;
+    const int seg = bs - b * a.segs;
     const long long tok_stride = static_cast<long long>(a.H) * kHeadSize;
     const long long unit_base = static_cast<long long>(b) * a.batch_stride +
+                                static_cast<long long>(seg) * a.seg_stride +
                                 static_cast<long long>(h) * kHeadSize;
-    const int nchunks = (a.T + kChunk - 1) / kChunk;
+    const int T = (seg == a.segs - 1) ? a.T_last : a.T;
+    const int nchunks = (T + kChunk - 1) / kChunk;
     if (wid < 8)
-        producer<kOutF32>(a, lds, tid, wid >> 2, wid & 3, h, unit_base, tok_stride, nchunks);
+        producer<kMode>(a, lds, tid, wid >> 2, wid & 3, h, unit_base, tok_stride, T, nchunks);
     else
-        consumer<kOutF32>(a, lds, tid & 63, wid - 8, unit, nchunks);
+        consumer<kMode>(a, lds, tid & 63, wid - 8, unit, nchunks);
+}
+
+// Sequential fold over the segments of one (batch, head): 256 threads x 16 state entries.
+__global__ __launch_bounds__(256) void combine_kernel(int H, int segs, const float* state_in,
+                                                      float* seg_state, const float* seg_decay,
+                                                      float* state_out) {
+    const int unit = blockIdx.x;                 // batch * H + head
+    const int b = unit / H;
+    const int h = unit - b * H;
+    const int t = threadIdx.x;
+    const int row = t >> 2;                      // key channel of this thread's 16 entries
+    float4 S[4];
+    if (state_in) {
+        const float4* s0 = reinterpret_cast<const float4*>(state_in + static_cast<long long>(unit) * 4096) + 4 * t;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) S[q] = s0[q];
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) S[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    for (int p = 0; p < segs; ++p) {
+        const long long su = (static_cast<long long>(b) * segs + p) * H + h;
+        float4* loc = reinterpret_cast<float4*>(seg_state + su * 4096) + 4 * t;
+        const float d = seg_decay[su * kHeadSize + row];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 l = loc[q];
+            loc[q] = S[q];                       // the state entering segment p
+            S[q] = make_float4(fmaf(d, S[q].x, l.x), fmaf(d, S[q].y, l.y), fmaf(d, S[q].z, l.z),
+                               fmaf(d, S[q].w, l.w));
+        }
+    }
+    if (state_out) {
+        float4* so = reinterpret_cast<float4*>(state_out + static_cast<long long>(unit) * 4096) + 4 * t;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) so[q] = S[q];
+    }
+}
+
+template <int kMode>
+hipError_t launch_mode(const Args& a, hipStream_t stream) {
+    const dim3 grid(static_cast<unsigned>(a.B) * static_cast<unsigned>(a.segs) * static_cast<unsigned>(a.H));
+    const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunked_kernel<kMode>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(chunked_kernel<kMode>, grid, dim3(kThreads), kLdsBytes, stream, a);
+    return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_chunked(const Args& a, bool out_f32, hipStream_t stream) {
-    const dim3 grid(static_cast<unsigned>(a.B) * static_cast<unsigned>(a.H));
-    hipError_t err;
-    if (out_f32) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunked_kernel<true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(chunked_kernel<true>, grid, dim3(kThreads), kLdsBytes, stream, a);
-    } else {
-        err = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunked_kernel<false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(chunked_kernel<false>, grid, dim3(kThreads), kLdsBytes, stream, a);
+hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream) {
+    switch (mode) {
+        case ChunkedMode::kBf16Out: return launch_mode<0>(a, stream);
+        case ChunkedMode::kF32Out: return launch_mode<1>(a, stream);
+        default: return launch_mode<2>(a, stream);
     }
+}
+
+hipError_t launch_combine_segments(int B, int H, int segs, const float* state_in, float* seg_state,
+                                   const float* seg_decay, float* state_out, hipStream_t stream) {
+    hipLaunchKernelGGL(combine_kernel, dim3(static_cast<unsigned>(B) * static_cast<unsigned>(H)),
+                       dim3(256), 0, stream, H, segs, state_in, seg_state, seg_decay, state_out);
     return hipGetLastError();
 }
 

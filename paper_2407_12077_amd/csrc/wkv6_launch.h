@@ -17,13 +17,30 @@ struct Args {
     void* out;
     float* state_out;         // may be nullptr (not written)
     long long batch_stride;   // elements between consecutive batches of r,k,v,x,out
+    // Token-axis segments (chunked kernel only).  Each sequence is cut into `segs` segments of T
+    // tokens (the last one T_last), seg_stride elements apart; a workgroup handles one
+    // (batch, segment, head) and indexes state_in / state_out / decay_out by
+    // (batch*segs + segment)*H + head.  segs == 1: T_last == T and the plain layout.
+    int segs;
+    int T_last;
+    long long seg_stride;
+    float* decay_out;         // may be nullptr; [B*segs][H][N] product of all decays of the unit
 };
+
+enum class ChunkedMode { kBf16Out, kF32Out, kStateOnly };
 
 // Token-by-token fp32 kernel; inputs bf16 or fp32, out always fp32.
 hipError_t launch_recurrent(const Args& a, bool in_bf16, hipStream_t stream);
 
-// Chunked matrix-core kernel; inputs bf16, out bf16 or fp32.
-hipError_t launch_chunked(const Args& a, bool out_f32, hipStream_t stream);
+// Chunked matrix-core kernel; inputs bf16, out bf16 or fp32, or (kStateOnly) no output at all:
+// only state_out and decay_out of every unit, from r-independent work.
+hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream);
+
+// Token-split support: folds the per-segment (decay, local state) pairs of every (batch, head)
+// into the state entering each segment, in place in `seg_state` ([B*segs][H][N][N]); writes the
+// final state of the sequence to state_out when it is not nullptr.
+hipError_t launch_combine_segments(int B, int H, int segs, const float* state_in, float* seg_state,
+                                   const float* seg_decay, float* state_out, hipStream_t stream);
 
 // T == 0: state_out = state_in (or zero).
 hipError_t launch_state_passthrough(const Args& a, hipStream_t stream);

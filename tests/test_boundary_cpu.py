@@ -82,3 +82,19 @@ def test_oracle_is_not_reachable_from_the_product():
                 text = open(os.path.join(dirpath, fn)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle|libwkv6_oracle|wkv6_oracle", text, re.M), \
                     f"{fn} reaches into the oracle"
+
+
+def test_split_helpers_and_validation():
+    lib = binding.load()
+    assert wkv.wkv6_split_segments(1, 131072, 32, 64) == 8          # 32 units on 256 CUs
+    assert wkv.wkv6_split_segments(8, 4096, 32, 64) == 1            # already one unit per CU
+    assert wkv.wkv6_split_segments(1, 1024, 32, 64) == 1            # too short to split
+    assert wkv.wkv6_split_workspace_bytes(1, 131072, 32, 64, 8) == 8 * 32 * (4096 + 64) * 4
+    assert wkv.wkv6_split_workspace_bytes(1, 100, 2, 64, 8) == 4 * 2 * (4096 + 64) * 4   # 32-token segments
+    assert wkv.wkv6_split_workspace_bytes(1, 100, 2, 32, 8) == -1
+    f = lib.wkv6_prefill_bf16_split
+    assert f(1, 4096, 2, 64, A, A, A, A, A, None, A, A, 1, 4, None, 0, None) == 1        # no workspace
+    assert f(1, 4096, 2, 64, A, A, A, A, A, None, A, A, 1, 4, A, 16, None) == 2           # too small
+    assert f(1, 4096, 2, 64, A, A, A, A, A, None, A, A, 9, 4, A, 1 << 30, None) == 3      # dtype code
+    assert f(1, 4096, 2, 64, A, A, A, A, A, None, A, A, 1, 0, A, 1 << 30, None) == 2      # segments < 1
+    assert f(1, 4096, 2, 32, A, A, A, A, A, None, A, A, 1, 4, A, 1 << 30, None) == 3      # N != 64

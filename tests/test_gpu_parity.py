@@ -193,6 +193,54 @@ def test_finch_c2_reduction(gpu_device):
     assert np.abs(st[0] - expect[:, :, None]).max() <= 3e-3  # k itself was rounded to bf16
 
 
+# ------------------------------------------------------------------ token-split variant
+def _run_split(inp, segments, out_dtype=torch.float32, want_state=True):
+    B, T, H, N = inp["r"].shape
+    r, k, v, x = (to_dev(inp[n], torch.bfloat16) for n in "rkvx")
+    u = to_dev(inp["u"], torch.float32)
+    s_in = to_dev(inp.get("state_in"), torch.float32)
+    out = torch.full((B, T, H, N), float("nan"), dtype=out_dtype, device="cuda")
+    s_out = torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda") if want_state else None
+    nbytes = wkv.wkv6_split_workspace_bytes(B, T, H, N, segments)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    code = wkv.WKV6_DTYPE_F32 if out_dtype == torch.float32 else wkv.WKV6_DTYPE_BF16
+    wkv.wkv6_prefill_bf16_split(B, T, H, N, r, k, v, x, u, s_in, out, s_out, code, segments, ws, nbytes)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64), (None if s_out is None else s_out.cpu().numpy().astype(np.float64))
+
+
+@pytest.mark.parametrize("T,segments", [(4096, 4), (5000, 4), (1000, 7), (333, 3), (64, 2), (40, 8), (8192, 16)])
+def test_split_matches_oracle(gpu_device, T, segments):
+    inp = make_inputs(scaled(CONFIGS[4], B=2, T=T, H=3), seed=700 + T)
+    o_ref, s_ref = wkv6_oracle(**inp)
+    o, s = _run_split(inp, segments)
+    eo, es = max_norm_err(o, o_ref), max_norm_err(s, s_ref)
+    print(f"split T={T} segments={segments}: err_out={eo:.3e} err_state={es:.3e}", flush=True)
+    assert eo <= TOL_BF16 and es <= TOL_BF16
+
+
+def test_split_with_long_memory_channels(gpu_device):
+    """Decays near 1 on half of the channels: the state entering a segment matters for its whole
+    length, and the product of decays over a segment is far from zero."""
+    inp = make_inputs(scaled(CONFIGS[5], B=1, T=4096, H=4), seed=71)
+    inp["state_in"] = (np.random.default_rng(72).standard_normal((1, 4, 64, 64)) * 0.5).astype(np.float32)
+    o_ref, s_ref = wkv6_oracle(**inp)
+    o, s = _run_split(inp, 8)
+    assert max_norm_err(o, o_ref) <= TOL_BF16 and max_norm_err(s, s_ref) <= TOL_BF16
+    inp["x"][:] = -np.inf                      # w == 1 everywhere: nothing is ever forgotten
+    o_ref, s_ref = wkv6_oracle(**inp)
+    o, s = _run_split(inp, 8)
+    assert max_norm_err(o, o_ref) <= TOL_BF16 and max_norm_err(s, s_ref) <= TOL_BF16
+
+
+def test_split_bf16_out_and_no_state_out(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[2], B=1, T=3000, H=2), seed=73)
+    o_ref, _ = wkv6_oracle(**inp)
+    o, s = _run_split(inp, 5, out_dtype=torch.bfloat16, want_state=False)
+    assert s is None and max_norm_err(o, o_ref) <= TOL_BF16 + BF16_OUT_ROUNDING
+
+
 # ------------------------------------------------------------------ full-size configs, sampled units
 def _unit_slice(inp, b, h):
     one = {n: np.ascontiguousarray(inp[n][b:b + 1, :, h:h + 1]) for n in "rkvx"}
@@ -249,3 +297,14 @@ def test_full_size_config_sampled_units(gpu_device, cfg_index, n_units):
             one[n] = one[n][:, :half]
         _, s_ref = wkv6_oracle(**one, nthreads=1)
         assert max_norm_err(s_half[b, h].cpu().numpy(), s_ref[0, 0]) <= TOL_BF16
+        # the token-split entry in the benchmark's configuration against the single-pass result
+        segs = wkv.wkv6_split_segments(B, T, H, N)
+        assert segs > 1
+        nbytes = wkv.wkv6_split_workspace_bytes(B, T, H, N, segs)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        o3 = torch.empty_like(out)
+        s3 = torch.empty_like(s_out)
+        wkv.wkv6_prefill_bf16_split(B, T, H, N, r, k, v, x, u, None, o3, s3, wkv.WKV6_DTYPE_F32, segs, ws, nbytes)
+        torch.cuda.synchronize()
+        assert max_norm_err(o3.cpu().numpy(), out.cpu().numpy()) <= TOL_BF16
+        assert max_norm_err(s3.cpu().numpy(), s_out.cpu().numpy()) <= TOL_BF16
