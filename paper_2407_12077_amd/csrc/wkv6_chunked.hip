@@ -89,6 +89,11 @@ __device__ __forceinline__ unsigned pack_h2(float a, float b) {
     return __builtin_bit_cast(unsigned, p);
 }
 
+// packed fp16 multiply of two channel pairs
+__device__ __forceinline__ unsigned mul_h2(unsigned a, unsigned b) {
+    return __builtin_bit_cast(unsigned, __builtin_bit_cast(half2v, a) * __builtin_bit_cast(half2v, b));
+}
+
 __device__ __forceinline__ unsigned short bf16_bits(float a) {
     return __builtin_bit_cast(unsigned short, static_cast<__bf16>(a));
 }
@@ -173,8 +178,8 @@ __device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int t0, con
 // chunk) to phase T (where the other groups' decay totals are known and the tiles are written).
 struct Prep {
     unsigned z2[4], rh[4], kh[4], ru[4], vt[4];           // finished fp16 pairs, one per token
-    float rp[2][4];                                        // r * prefix product inside the group
-    float ks[2][4];                                        // k * suffix product inside the group
+    unsigned rp[4];            // r * prefix product inside the group, fp16 pair (2 channels)
+    unsigned ks[4];            // k * suffix product inside the group, fp16 pair
 };
 
 // ------------------------------------------------------------------------------------------
@@ -245,7 +250,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             w[0][s] = decay_of(bf16_lo(cur.x[s]));
             w[1][s] = decay_of(bf16_hi(cur.x[s]));
         }
-        float r4[2][4], k4[2][4], gtot[2];
+        float r4[2][4], k4[2][4], rp[2][4], ks[2][4], gtot[2];
 #pragma unroll
         for (int ch = 0; ch < 2; ++ch) {
             const float p2 = w[ch][0] * w[ch][1];            // prefix of token 2
@@ -258,18 +263,20 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                 r4[ch][s] = ch ? bf16_hi(cur.r[s]) : bf16_lo(cur.r[s]);
                 k4[ch][s] = ch ? bf16_hi(cur.k[s]) : bf16_lo(cur.k[s]);
             }
-            pr.rp[ch][0] = r4[ch][0];
-            pr.rp[ch][1] = r4[ch][1] * w[ch][0];
-            pr.rp[ch][2] = r4[ch][2] * p2;
-            pr.rp[ch][3] = r4[ch][3] * p3;
-            pr.ks[ch][0] = k4[ch][0] * s0;
-            pr.ks[ch][1] = k4[ch][1] * s1;
-            pr.ks[ch][2] = k4[ch][2] * w[ch][3];
-            pr.ks[ch][3] = k4[ch][3];
+            rp[ch][0] = r4[ch][0];
+            rp[ch][1] = r4[ch][1] * w[ch][0];
+            rp[ch][2] = r4[ch][2] * p2;
+            rp[ch][3] = r4[ch][3] * p3;
+            ks[ch][0] = k4[ch][0] * s0;
+            ks[ch][1] = k4[ch][1] * s1;
+            ks[ch][2] = k4[ch][2] * w[ch][3];
+            ks[ch][3] = k4[ch][3];
         }
         *reinterpret_cast<float2*>(lds + kG + (g8 * 64 + 2 * cp) * 4) = make_float2(gtot[0], gtot[1]);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
+            pr.rp[s] = pack_h2(rp[0][s], rp[1][s]);
+            pr.ks[s] = pack_h2(ks[0][s], ks[1][s]);
             pr.rh[s] = pack_h2(r4[0][s], r4[1][s]);
             pr.kh[s] = pack_h2(k4[0][s], k4[1][s]);
             pr.ru[s] = pack_h2(r4[0][s] * u0, r4[1][s] * u1);
@@ -317,32 +324,31 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             m8[ch] = q8 ? before : after;                 // level 8: inside the 8-token block
             if (g8 == 0) *reinterpret_cast<float*>(lds + kD + (2 * cp + ch) * 4) = o[0] * m_kt[ch];
         }
+        // the multipliers as fp16 channel pairs: one packed multiply per tile entry
+        const unsigned h_rt = pack_h2(m_rt[0], m_rt[1]);
+        const unsigned h_kt = pack_h2(m_kt[0], m_kt[1]);
+        const unsigned h16 = pack_h2(m16[0], m16[1]);
+        const unsigned h8 = pack_h2(m8[0], m8[1]);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int row = (4 * g8 + s) * kRow;
             const int nat = row + 4 * cp;                    // natural channel order
             if constexpr (kStateOnly) {
                 lds_write_u32(lds, kVT + nat, pr.vt[s]);
-                lds_write_u32(lds, kKT + nat, pack_h2(pr.ks[0][s] * m_kt[0], pr.ks[1][s] * m_kt[1]));
+                lds_write_u32(lds, kKT + nat, mul_h2(pr.ks[s], h_kt));
                 continue;
             }
             // level 4: the even group of an 8-block holds keys, the odd one queries
-            lds_write_u32(lds, kZ4 + nat, q4 ? pack_h2(pr.rp[0][s], pr.rp[1][s]) : pack_h2(pr.ks[0][s], pr.ks[1][s]));
+            lds_write_u32(lds, kZ4 + nat, q4 ? pr.rp[s] : pr.ks[s]);
             lds_write_u32(lds, kZ2 + nat, pr.z2[s]);
             lds_write_u32(lds, kRH + nat, pr.rh[s]);
             lds_write_u32(lds, kKH + nat, pr.kh[s]);
             lds_write_u32(lds, kRU + nat, pr.ru[s]);
             lds_write_u32(lds, kVT + nat, pr.vt[s]);
-            lds_write_u32(lds, kRT + row + rt_col * 2, pack_h2(pr.rp[0][s] * m_rt[0], pr.rp[1][s] * m_rt[1]));
-            lds_write_u32(lds, kKT + nat, pack_h2(pr.ks[0][s] * m_kt[0], pr.ks[1][s] * m_kt[1]));
-            {
-                const float a0 = q16 ? pr.rp[0][s] : pr.ks[0][s], a1 = q16 ? pr.rp[1][s] : pr.ks[1][s];
-                lds_write_u32(lds, kZ16 + nat, pack_h2(a0 * m16[0], a1 * m16[1]));
-            }
-            {
-                const float a0 = q8 ? pr.rp[0][s] : pr.ks[0][s], a1 = q8 ? pr.rp[1][s] : pr.ks[1][s];
-                lds_write_u32(lds, kZ8 + nat, pack_h2(a0 * m8[0], a1 * m8[1]));
-            }
+            lds_write_u32(lds, kRT + row + rt_col * 2, mul_h2(pr.rp[s], h_rt));
+            lds_write_u32(lds, kKT + nat, mul_h2(pr.ks[s], h_kt));
+            lds_write_u32(lds, kZ16 + nat, mul_h2(q16 ? pr.rp[s] : pr.ks[s], h16));
+            lds_write_u32(lds, kZ8 + nat, mul_h2(q8 ? pr.rp[s] : pr.ks[s], h8));
         }
     };
 
