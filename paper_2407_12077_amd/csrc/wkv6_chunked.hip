@@ -72,7 +72,7 @@ enum : int {
     kG = 12 * kTile,                       // per 4-token group decay products [8][64] fp32
     kD = kG + 8 * 64 * 4,                  // whole-chunk decay product [64] fp32
     kO = kD + 64 * 4,                      // output staging [32 tokens][64]
-    kBuf = kO + kChunk * kORowF32 * 4,
+    kBuf = (kO + kChunk * kORowF32 * 4 + 1023) / 1024 * 1024,
     kLdsBytes = 2 * kBuf
 };
 static_assert(kBuf % 16 == 0 && kLdsBytes <= 160 * 1024, "LDS budget");
@@ -420,12 +420,17 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // and are issued here, off the critical path, because issuing blocks while the memory
     // pipeline is full.
     auto phase_t = [&](int c, Raw& mine) {
+        __builtin_amdgcn_s_setprio(0);           // the scoring group is the busier one: let it go first
         if (c < nchunks) write_tiles();
-        if (c + 4 < nchunks) load_rows<kStateOnly>(mine, st, (c + 4) * kChunk, voff);
+        // issued unconditionally (past the end the descriptor is empty and the loads return
+        // zeros without touching memory): every path then has the same number of loads in
+        // flight, which lets the wait before the next digest skip the youngest sixteen
+        load_rows<kStateOnly>(mine, st, (c + 4) * kChunk, voff);
     };
     // Phase S of chunk c: scores, decays of this group's next chunk (c+2, raw registers `next`),
     // then the finished rows of chunk c-2 (last: nothing here waits for the stores' acknowledgement).
     auto phase_s = [&](int c, Raw& next) {
+        __builtin_amdgcn_s_setprio(2);
         if constexpr (!kStateOnly)
             if (c >= 0 && c < nchunks) scores();
         if (c + 2 < nchunks) digest(c + 2, next);
@@ -440,7 +445,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     const int nwin = (nchunks + 6) & ~3;
     if (pg == 0) {
         load_rows<kStateOnly>(raw_a, st, 0, voff);
-        if (2 < nchunks) load_rows<kStateOnly>(raw_b, st, 2 * kChunk, voff);
+        load_rows<kStateOnly>(raw_b, st, 2 * kChunk, voff);
         digest(0, raw_a);
         __syncthreads();                                                        // start barrier
 #pragma clang loop unroll(disable)
@@ -455,8 +460,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             __syncthreads();                                                    // window barrier
         }
     } else {
-        if (1 < nchunks) load_rows<kStateOnly>(raw_a, st, kChunk, voff);
-        if (3 < nchunks) load_rows<kStateOnly>(raw_b, st, 3 * kChunk, voff);
+        load_rows<kStateOnly>(raw_a, st, kChunk, voff);
+        load_rows<kStateOnly>(raw_b, st, 3 * kChunk, voff);
         __syncthreads();                                                        // start barrier
         phase_s(-1, raw_a);                      // window 0: only the digest of chunk 1 applies
         __syncthreads();                                                        // window barrier
