@@ -49,7 +49,8 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
 constexpr int kChunk = 32;                 // tokens per chunk
-constexpr int kThreads = 64 * 12;
+constexpr int kProducerGroups = 3;         // 4 waves each
+constexpr int kThreads = 64 * (4 * kProducerGroups + 4);
 constexpr int kRow = 160;                  // fp16 tile row stride in bytes (64 halfs + 16 pad)
 constexpr int kTile = kChunk * kRow;       // one [32 tokens][64 channels] tile
 constexpr int kORowF32 = 68;               // output staging row stride, fp32 mode (floats)
@@ -190,7 +191,6 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                                          long long unit_base, long long tok_stride, int T, int nchunks) {
     constexpr bool kOutF32 = kMode == 1;
     constexpr bool kStateOnly = kMode == 2;
-    char* lds = lds_all + pg * kBuf;         // this group's tiles
     const int lane = tid & 63;
     const int gtid = tid & 255;              // thread inside the group
     const int cp = lane & 31;                // channel pair: channels 2cp, 2cp+1
@@ -219,7 +219,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 
     // the score block above the diagonal that the A.V product still touches, (t-block 0,
     // i-block 1), stays zero for good in both partial score tiles: 2 x 16x16 halfs = 256 dwords
-    if constexpr (!kStateOnly) {
+    if (!kStateOnly && pg < 2) {
+        char* lds = lds_all + pg * kBuf;
         const int which = gtid >> 7;                 // A0 / A1
         const int e = gtid & 127;                    // row = e>>3, column pair = e&7
         lds_write_u32(lds, (which ? kA1 : kA0) + (e >> 3) * kRow + (16 + 2 * (e & 7)) * 2, 0u);
@@ -237,6 +238,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // Phase S, part 2.  Digest the raw inputs in `cur` (chunk c): decays, their products inside
     // the thread's 4-token group (published in G), and every operand that needs nothing else.
     auto digest = [&](int c, Raw& cur) {
+        char* lds = lds_all + (c & 1) * kBuf;
         const int t0 = c * kChunk;
         if (t0 + kChunk > T) {
             // last, partial chunk: tokens past the end were read as zeros; give them w = 1
@@ -290,7 +292,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     };
 
     // Phase T: multipliers from the other groups' decay totals, then every operand tile.
-    auto write_tiles = [&]() {
+    auto write_tiles = [&](int c) {
+        char* lds = lds_all + (c & 1) * kBuf;
         float m_rt[2], m_kt[2], m16[2], m8[2];
         float2 own[8];
 #pragma unroll
@@ -356,7 +359,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // split in two halves (kk), each wave writes its partial scores to tile A0 or A1 and the
     // consumers add the two products.  Wave wq: diagonal block wq&1, channel half wq>>1; the
     // waves with an even wq also take the level-16 block (t-block 1, i-block 0).
-    auto scores = [&]() {
+    auto scores = [&](int c) {
+        char* lds = lds_all + (c & 1) * kBuf;
         const int q = wq & 1;
         const int kk = wq >> 1;
         const int at = kk ? kA1 : kA0;
@@ -397,6 +401,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // Phase S, part 2.  Finished output rows of chunk c (staged by the consumers): full
     // 128-byte (bf16) rows to HBM, 8 threads per row.
     auto store_rows = [&](int c) {
+        const char* lds = lds_all + (c & 1) * kBuf;
         const int row = gtid >> 3;
         const int col = 8 * (gtid & 7);
         const int t = c * kChunk + row;
@@ -415,74 +420,49 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         }
     };
 
-    // Phase T of chunk c: its tiles, then the HBM loads of this group's chunk after next (c+4)
-    // into the raw registers that chunk c itself used; they stay in flight for three windows
-    // and are issued here, off the critical path, because issuing blocks while the memory
-    // pipeline is full.
-    auto phase_t = [&](int c, Raw& mine) {
-        __builtin_amdgcn_s_setprio(0);           // the scoring group is the busier one: let it go first
-        if (c < nchunks) write_tiles();
-        // issued unconditionally (past the end the descriptor is empty and the loads return
-        // zeros without touching memory): every path then has the same number of loads in
-        // flight, which lets the wait before the next digest skip the youngest sixteen
-        load_rows<kStateOnly>(mine, st, (c + 4) * kChunk, voff);
-    };
-    // Phase S of chunk c: scores, decays of this group's next chunk (c+2, raw registers `next`),
-    // then the finished rows of chunk c-2 (last: nothing here waits for the stores' acknowledgement).
-    auto phase_s = [&](int c, Raw& next) {
-        __builtin_amdgcn_s_setprio(2);
-        if constexpr (!kStateOnly)
-            if (c >= 0 && c < nchunks) scores();
-        if (c + 2 < nchunks) digest(c + 2, next);
-        if constexpr (!kStateOnly)
+    // A group spends three consecutive windows on each of its chunks c = pg, pg+3, ...:
+    //   window c    phase D: decays and group products of chunk c from the raw registers, then
+    //               the HBM loads of the group's next chunk (c+3) into the same registers; they
+    //               stay in flight for three windows.  Issued unconditionally: past the end the
+    //               descriptor is empty and the loads return zeros without touching memory.
+    //   window c+1  phase T: multipliers from all groups' decay totals, every operand tile.
+    //   window c+2  phase S: score MFMAs, and the finished output rows of chunk c-2.
+    // The three groups are one window apart, so every window sees one group in each phase
+    // next to the consumers: vector-ALU, LDS and matrix-core work of different chunks overlap.
+    const int nwin = (nchunks + 6) / 3 * 3;
+    // one chunk of this group through its three windows; `buf` holds its raw inputs and is
+    // refilled with the group's chunk after next (six chunks ahead) right after the digest
+    auto cycle = [&](int c, Raw& buf) {
+        if (c < nchunks) digest(c, buf);
+        load_rows<kStateOnly>(buf, st, (c + 6) * kChunk, voff);
+        __syncthreads();                                                        // window barrier
+        if (c < nchunks) write_tiles(c);
+        __syncthreads();                                                        // window barrier
+        if constexpr (!kStateOnly) {
+            if (c < nchunks) scores(c);
             if (c >= 2 && c - 2 < nchunks) store_rows(c - 2);
+        }
+        __syncthreads();                                                        // window barrier
     };
-
-    // Windows 0 .. nwin-1 (nwin a multiple of 4); group 0 runs T in even windows and S in odd
-    // ones, group 1 the other way round, so each group's loop is a plain T / S sequence with a
-    // barrier after every phase.  The two raw register sets alternate between consecutive chunks
-    // of the group, which the loops spell out by handling two of them per iteration.
-    const int nwin = (nchunks + 6) & ~3;
-    if (pg == 0) {
-        load_rows<kStateOnly>(raw_a, st, 0, voff);
-        load_rows<kStateOnly>(raw_b, st, 2 * kChunk, voff);
-        digest(0, raw_a);
-        __syncthreads();                                                        // start barrier
+    load_rows<kStateOnly>(raw_a, st, pg * kChunk, voff);
+    load_rows<kStateOnly>(raw_b, st, (pg + 3) * kChunk, voff);
+    __syncthreads();                                                            // start barrier
+    int done = 0;                                                               // windows passed
+    for (; done < pg; ++done) {
+        __syncthreads();                                                        // window barrier
+    }
+    int c = pg;
 #pragma clang loop unroll(disable)
-        for (int c = 0; c < nwin; c += 4) {
-            phase_t(c, raw_a);
-            __syncthreads();                                                    // window barrier
-            phase_s(c, raw_b);
-            __syncthreads();                                                    // window barrier
-            phase_t(c + 2, raw_b);
-            __syncthreads();                                                    // window barrier
-            phase_s(c + 2, raw_a);
-            __syncthreads();                                                    // window barrier
-        }
-    } else {
-        load_rows<kStateOnly>(raw_a, st, kChunk, voff);
-        load_rows<kStateOnly>(raw_b, st, 3 * kChunk, voff);
-        __syncthreads();                                                        // start barrier
-        phase_s(-1, raw_a);                      // window 0: only the digest of chunk 1 applies
-        __syncthreads();                                                        // window barrier
-        int c = 1;
-#pragma clang loop unroll(disable)
-        for (; c + 4 < nwin; c += 4) {
-            phase_t(c, raw_a);
-            __syncthreads();                                                    // window barrier
-            phase_s(c, raw_b);
-            __syncthreads();                                                    // window barrier
-            phase_t(c + 2, raw_b);
-            __syncthreads();                                                    // window barrier
-            phase_s(c + 2, raw_a);
-            __syncthreads();                                                    // window barrier
-        }
-        // the last three windows nwin-3 .. nwin-1 (only row stores can still be due)
-        phase_t(c, raw_a);
-        __syncthreads();                                                        // window barrier
-        phase_s(c, raw_b);
-        __syncthreads();                                                        // window barrier
-        phase_t(c + 2, raw_b);
+    for (; c + 5 < nwin; c += 6) {
+        cycle(c, raw_a);
+        cycle(c + 3, raw_b);
+        done += 6;
+    }
+    if (c + 2 < nwin) {
+        cycle(c, raw_a);
+        done += 3;
+    }
+    for (; done < nwin; ++done) {
         __syncthreads();                                                        // window barrier
     }
 }
@@ -521,12 +501,12 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
     const int tr_lane = (8 * g4 + (l16 >> 2)) * kRow + 8 * (l16 & 3);
 
     __syncthreads();                                                            // start barrier
-    const int nwin = (nchunks + 6) & ~3;
+    const int nwin = (nchunks + 6) / 3 * 3;
 #pragma clang loop unroll(disable)
     for (int n = 0; n < nwin; ++n) {
-        if (!kStateOnly && n >= 2 && n - 2 < nchunks) {
-            // chunk n-2: o += A V (two partial score tiles), then stage for the producers' stores
-            char* lds = lds_all + (n & 1) * kBuf;
+        if (!kStateOnly && n >= 3 && n - 3 < nchunks) {
+            // chunk n-3: o += A V (two partial score tiles), then stage for the producers' stores
+            char* lds = lds_all + ((n - 3) & 1) * kBuf;
 #pragma unroll
             for (int tq = 0; tq < 2; ++tq) {
                 const int off = (16 * tq + l16) * kRow + 16 * g4;
@@ -544,9 +524,9 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
                 }
             }
         }
-        if (n >= 1 && n - 1 < nchunks) {
-            // chunk n-1: the state chain
-            const char* lds = lds_all + ((n - 1) & 1) * kBuf;
+        if (n >= 2 && n - 2 < nchunks) {
+            // chunk n-2: the state chain
+            const char* lds = lds_all + (n & 1) * kBuf;
             // inter-chunk read: o[t][j] = sum_n (r_t W(t,-1))[n] S[n][j]; the state registers,
             // rounded to fp16, are the B operand (k-slot order = the r tile's column permutation)
             if constexpr (!kStateOnly) {
@@ -609,10 +589,10 @@ __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
                                 static_cast<long long>(h) * kHeadSize;
     const int T = (seg == a.segs - 1) ? a.T_last : a.T;
     const int nchunks = (T + kChunk - 1) / kChunk;
-    if (wid < 8)
+    if (wid < 4 * kProducerGroups)
         producer<kMode>(a, lds, tid, wid >> 2, wid & 3, h, unit_base, tok_stride, T, nchunks);
     else
-        consumer<kMode>(a, lds, tid & 63, wid - 8, unit, nchunks);
+        consumer<kMode>(a, lds, tid & 63, wid - 4 * kProducerGroups, unit, nchunks);
 }
 
 // Sequential fold over the segments of one (batch, head): 256 threads x 16 state entries.
