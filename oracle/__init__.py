@@ -8,6 +8,9 @@ and never imports it.
                   threaded over (batch, head) units.
 ``wkv6_numpy``    an independent NumPy fp64 twin of the same recurrence
                   (``wkv6_numpy.py``), used to cross-check the C build.
+``finch_c2_oracle`` / ``finch_c2_numpy``
+                  the Finch-C2 form of the time mix (key times one minus the decay, second
+                  value added to the read-out, no bonus), ``finch_c2_oracle.c`` and its twin.
 """
-from .cbuild import build_oracle, wkv6_oracle  # noqa: F401
-from .wkv6_numpy import wkv6_numpy  # noqa: F401
+from .cbuild import build_oracle, finch_c2_oracle, wkv6_oracle  # noqa: F401
+from .wkv6_numpy import finch_c2_numpy, wkv6_numpy  # noqa: F401

@@ -7,16 +7,18 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "wkv6_oracle.c")
+_SRC_C2 = os.path.join(_HERE, "finch_c2_oracle.c")
 _LIB = os.path.join(_HERE, "libwkv6_oracle.so")
 _handle = None
 
 
 def build_oracle(force=False):
-    """Compile ``wkv6_oracle.c`` with the host C compiler (no fast-math)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    """Compile the oracle's C sources with the host C compiler (no fast-math)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
+        os.path.getmtime(_SRC), os.path.getmtime(_SRC_C2))
     if force or stale:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-pthread",
-               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC_C2, "-lm"]
         subprocess.check_call(cmd)
     return _LIB
 
@@ -29,6 +31,8 @@ def _lib():
         dp = ctypes.POINTER(ctypes.c_double)
         lib.wkv6_oracle_f64.restype = ctypes.c_int
         lib.wkv6_oracle_f64.argtypes = [ctypes.c_int] * 4 + [fp] * 6 + [dp, dp, ctypes.c_int]
+        lib.finch_c2_oracle_f64.restype = ctypes.c_int
+        lib.finch_c2_oracle_f64.argtypes = [ctypes.c_int] * 4 + [fp] * 6 + [dp, dp, ctypes.c_int]
         _handle = lib
     return _handle
 
@@ -70,4 +74,36 @@ def wkv6_oracle(r, k, v, x, u, state_in=None, nthreads=None):
         out.ctypes.data_as(dp), sout.ctypes.data_as(dp), int(nthreads))
     if rc != 0:
         raise RuntimeError(f"wkv6_oracle_f64 failed with status {rc}")
+    return out, sout
+
+
+def finch_c2_oracle(r, kbar, v, x, uprime, state_in=None, nthreads=None):
+    """Sequential fp64 Finch-C2 time mix per head (Finch-C2 Time Mixing equations).
+
+    k_t = kbar_t (1 - w_t);  o_t = r_t . S_{t-1} + u'_t;  S_t = diag(w_t) S_{t-1} + k_t^T v_t.
+    r, kbar, v, x, uprime : [B, T, H, N]; state_in : [B, H, N, N] or None.
+    Returns (out [B,T,H,N] float64, state_out [B,H,N,N] float64).
+    """
+    r = np.asarray(r)
+    B, T, H, N = r.shape
+    r = _f32(r, (B, T, H, N), "r")
+    kbar = _f32(kbar, (B, T, H, N), "kbar")
+    v = _f32(v, (B, T, H, N), "v")
+    x = _f32(x, (B, T, H, N), "x")
+    uprime = _f32(uprime, (B, T, H, N), "uprime")
+    s0 = None if state_in is None else _f32(state_in, (B, H, N, N), "state_in")
+    out = np.empty((B, T, H, N), dtype=np.float64)
+    sout = np.empty((B, H, N, N), dtype=np.float64)
+    if nthreads is None:
+        nthreads = os.cpu_count() or 1
+    fp = ctypes.POINTER(ctypes.c_float)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = _lib().finch_c2_oracle_f64(
+        B, T, H, N,
+        r.ctypes.data_as(fp), kbar.ctypes.data_as(fp), v.ctypes.data_as(fp),
+        x.ctypes.data_as(fp), uprime.ctypes.data_as(fp),
+        s0.ctypes.data_as(fp) if s0 is not None else None,
+        out.ctypes.data_as(dp), sout.ctypes.data_as(dp), int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"finch_c2_oracle_f64 failed with status {rc}")
     return out, sout
