@@ -24,15 +24,16 @@ MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 MFMA
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each
 # scaled by the same counter's reading for a plain copy kernel); see profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 262 330 KiB x 2.0 (copy calibration) + WRITE_SIZE 135 168 KiB x 1.0
-    "config2:wkv6_prefill_bf16": int(262330 * 1024 * 2.0 + 135168 * 1024 * 1.0),
+    # FETCH_SIZE 262 262 KiB x 2.0 (copy calibration) + WRITE_SIZE 135 168 KiB x 1.0
+    "config2:wkv6_prefill_bf16": int(262262 * 1024 * 2.0 + 135168 * 1024 * 1.0),
 }
 
 
-def algorithmic_bytes(cfg, out_bytes, state_in, state_out=True):
-    """Bytes the method must move per launch: r,k,v,x read once in bf16, the output written
-    once, plus the fp32 state of every (batch, head) unit read and/or written once."""
-    per_token_head = 4 * cfg.N * 2 + cfg.N * out_bytes
+def algorithmic_bytes(cfg, out_bytes, state_in, state_out=True, streams_in=4):
+    """Bytes the method must move per launch: r,k,v,x (and u' in the Finch-C2 form) read once in
+    bf16, the output written once, plus the fp32 state of every (batch, head) unit read and/or
+    written once."""
+    per_token_head = streams_in * cfg.N * 2 + cfg.N * out_bytes
     state = cfg.B * cfg.H * cfg.N * cfg.N * 4
     return cfg.token_heads * per_token_head + state * (int(state_in) + int(state_out))
 
@@ -42,16 +43,20 @@ def algorithmic_flops(cfg, chunk=64):
     return cfg.token_heads * (4 * chunk * cfg.N + 4 * cfg.N * cfg.N)
 
 
-def cpu_baseline(cfg, inp):
+def cpu_baseline(cfg, inp, finch_c2=False):
     """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample."""
-    from oracle import wkv6_oracle
+    from oracle import finch_c2_oracle, wkv6_oracle
     cores = min(os.cpu_count() or 1, 16)
     budget_token_heads = 4_000_000              # about 10 s of CPU work on 8-16 cores
     nb = max(1, min(cfg.B, budget_token_heads // (cfg.T * cfg.H)))
     sample = {n: inp[n][:nb] for n in ("r", "k", "v", "x")}
     s0 = None if inp["state_in"] is None else inp["state_in"][:nb]
     t0 = time.perf_counter()
-    wkv6_oracle(sample["r"], sample["k"], sample["v"], sample["x"], inp["u"], s0, nthreads=cores)
+    if finch_c2:
+        finch_c2_oracle(sample["r"], sample["k"], sample["v"], sample["x"], inp["uprime"][:nb], s0,
+                        nthreads=cores)
+    else:
+        wkv6_oracle(sample["r"], sample["k"], sample["v"], sample["x"], inp["u"], s0, nthreads=cores)
     dt = time.perf_counter() - t0
     return {"value": nb * cfg.T / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"first {nb} of {cfg.B} sequences of the same workload "
@@ -66,7 +71,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--entry", default="wkv6_prefill_bf16",
                     choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent",
-                             "wkv6_prefill_bf16_split"])
+                             "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
+                             "wkv6_finch_c2_prefill_bf16_f32out"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 512 MiB device copy (calibrates rocprofv3 byte counters)")
@@ -77,7 +83,7 @@ def main():
 
     import torch
     import paper_2407_12077_amd as wkv
-    from paper_2407_12077_amd.workloads import CONFIGS, make_inputs
+    from paper_2407_12077_amd.workloads import CONFIGS, make_inputs, make_uprime
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -92,7 +98,11 @@ def main():
     r, k, v, x = (dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "x"))
     u = dev(inp["u"], torch.float32)
     s_in = dev(inp["state_in"], torch.float32)
-    out_f32 = args.entry not in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_split")
+    finch_c2 = args.entry.startswith("wkv6_finch_c2")
+    if finch_c2:
+        inp["uprime"] = make_uprime(cfg)
+        up = dev(inp["uprime"], torch.bfloat16)
+    out_f32 = args.entry not in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16")
     out = torch.empty((B, T, H, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
     s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
     fn = getattr(wkv, args.entry)
@@ -107,6 +117,11 @@ def main():
         def step():
             fn(B, T, H, N, r, k, v, x, u, s_in, out, s_out, wkv.WKV6_DTYPE_BF16, segments, ws, ws_bytes,
                stream.cuda_stream)
+    elif finch_c2:
+        segments = 1
+
+        def step():
+            fn(B, T, H, N, r, k, v, x, up, s_in, out, s_out, stream.cuda_stream)
     else:
         segments = 1
 
@@ -135,7 +150,7 @@ def main():
     kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
     ms_per_step = wall * 1e3 / args.steps
 
-    abytes = algorithmic_bytes(cfg, 4 if out_f32 else 2, s_in is not None)
+    abytes = algorithmic_bytes(cfg, 4 if out_f32 else 2, s_in is not None, streams_in=5 if finch_c2 else 4)
     aflops = algorithmic_flops(cfg)
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
     key = f"config{args.config}:{args.entry}"
@@ -158,12 +173,13 @@ def main():
                    "entry": args.entry, "segments": segments, "global_batch": B, "seq_len": T},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(key),
-                     "kernel_ms_avg": kernel_ms, "kernel_ms_min": min(per_launch_ms),
+                     "kernel_ms_avg": kernel_ms, "kernel_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
+                     "kernel_ms_min": min(per_launch_ms),
                      "algorithmic_bytes": abytes,
                      "mfma_frac": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, inp)
+        result["cpu_baseline"] = cpu_baseline(cfg, inp, finch_c2)
     print(json.dumps(result))
 
 

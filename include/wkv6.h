@@ -117,6 +117,40 @@ long long wkv6_split_workspace_bytes(int B, int T, int H, int N, int segments);
 /* Segment count this library would pick for the shape on a 256-CU MI355X (1 = do not split). */
 int wkv6_split_segments(int B, int T, int H, int N);
 
+/*
+ * Finch-C2 form of the same time mix (paper: Method, "Finch-C2 Time Mixing": the key is
+ * multiplied by one minus the decay, and a data-dependent second value u'_t replaces Finch's
+ * bonus in the read-out), fused into the chunked kernel:
+ *
+ *     w_t = exp(-exp(x_t)),   k_t = kbar_t * (1 - w_t)
+ *     o_t = r_t . S_{t-1} + u'_t
+ *     S_t = diag(w_t) S_{t-1} + k_t^T v_t
+ *
+ *   kbar    [B][T][H][N] bf16  the projected key BEFORE its (1 - w) factor; the factor is applied
+ *                              in fp32 from the decay the kernel computes anyway
+ *   uprime  [B][T][H][N] bf16  second value, added to the fp32 read-out before its one rounding
+ * There is no u argument.  Everything else (layouts, state, alignment, T and B edge cases,
+ * value range, errors) is as for wkv6_prefill_bf16.  The LayerNorm over the concatenated heads
+ * and the output projection that follow in the paper are not part of this call.
+ */
+int wkv6_finch_c2_prefill_bf16(int B, int T, int H, int N,
+                               const void *r, const void *kbar, const void *v, const void *x,
+                               const void *uprime, const float *state_in,
+                               void *out, float *state_out, void *stream);
+
+/* Same, `out` written in fp32. */
+int wkv6_finch_c2_prefill_bf16_f32out(int B, int T, int H, int N,
+                                      const void *r, const void *kbar, const void *v, const void *x,
+                                      const void *uprime, const float *state_in,
+                                      float *out, float *state_out, void *stream);
+
+/* Same for a window of a larger buffer (see wkv6_prefill_bf16_strided); uprime is strided like out. */
+int wkv6_finch_c2_prefill_bf16_strided(int B, int T, int H, int N,
+                                       const void *r, const void *kbar, const void *v, const void *x,
+                                       const void *uprime, const float *state_in,
+                                       void *out, float *state_out,
+                                       long long batch_stride, int out_dtype, void *stream);
+
 /* All-fp32 tensors.  Token-by-token kernel with the state in fp32 registers. */
 int wkv6_prefill_f32(int B, int T, int H, int N,
                      const float *r, const float *k, const float *v, const float *x,

@@ -17,8 +17,9 @@ WKV6_DTYPE_F32 = 1
 
 EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_strided",
            "wkv6_prefill_f32", "wkv6_prefill_bf16_recurrent", "wkv6_prefill_bf16_split",
-           "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_status_string",
-           "wkv6_version")
+           "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_finch_c2_prefill_bf16",
+           "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_strided",
+           "wkv6_status_string", "wkv6_version")
 
 _lib = None
 
@@ -40,12 +41,15 @@ def load():
         vp, i, ll = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
         common = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_f32",
-                     "wkv6_prefill_bf16_recurrent"):
+                     "wkv6_prefill_bf16_recurrent", "wkv6_finch_c2_prefill_bf16",
+                     "wkv6_finch_c2_prefill_bf16_f32out"):
             fn = getattr(lib, name)
             fn.restype = i
             fn.argtypes = common + [vp]
         lib.wkv6_prefill_bf16_strided.restype = i
         lib.wkv6_prefill_bf16_strided.argtypes = common + [ll, i, vp]
+        lib.wkv6_finch_c2_prefill_bf16_strided.restype = i
+        lib.wkv6_finch_c2_prefill_bf16_strided.argtypes = common + [ll, i, vp]
         lib.wkv6_prefill_bf16_split.restype = i
         lib.wkv6_prefill_bf16_split.argtypes = common + [i, i, vp, ll, vp]
         lib.wkv6_split_workspace_bytes.restype = ll
@@ -120,6 +124,22 @@ def wkv6_prefill_f32(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream
 
 def wkv6_prefill_bf16_recurrent(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):
     _call("wkv6_prefill_bf16_recurrent", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream)
+
+
+def wkv6_finch_c2_prefill_bf16(B, T, H, N, r, kbar, v, x, uprime, state_in, out, state_out, stream=None):
+    _call("wkv6_finch_c2_prefill_bf16", B, T, H, N, r, kbar, v, x, uprime, state_in, out, state_out, stream)
+
+
+def wkv6_finch_c2_prefill_bf16_f32out(B, T, H, N, r, kbar, v, x, uprime, state_in, out, state_out,
+                                      stream=None):
+    _call("wkv6_finch_c2_prefill_bf16_f32out", B, T, H, N, r, kbar, v, x, uprime, state_in, out,
+          state_out, stream)
+
+
+def wkv6_finch_c2_prefill_bf16_strided(B, T, H, N, r, kbar, v, x, uprime, state_in, out, state_out,
+                                       batch_stride, out_dtype, stream=None):
+    _call("wkv6_finch_c2_prefill_bf16_strided", B, T, H, N, r, kbar, v, x, uprime, state_in, out,
+          state_out, stream, ctypes.c_longlong(batch_stride), int(out_dtype))
 
 
 def wkv6_version():

@@ -11,18 +11,21 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<std::uintptr_t>
 
 enum class Path { kChunked, kRecurrent };
 
+// `uprime` selects the form: nullptr = Finch (bonus u), otherwise Finch-C2 (u unused, may be null).
 int run(int B, int T, int H, int N, const void* r, const void* k, const void* v, const void* x,
         const float* u, const float* state_in, void* out, float* state_out,
-        long long batch_stride, bool in_bf16, bool out_f32, Path path, void* stream) {
+        long long batch_stride, bool in_bf16, bool out_f32, Path path, void* stream,
+        const void* uprime = nullptr, bool finch_c2 = false) {
     if (N != wkv6::kHeadSize) return WKV6_ERR_UNSUPPORTED;
     if (B < 0 || T < 0 || H < 1 || H > 262144) return WKV6_ERR_SHAPE;   // 32-bit row offsets in the kernels
-    if (!u) return WKV6_ERR_NULL;
+    if (!finch_c2 && !u) return WKV6_ERR_NULL;
     if (B == 0) return WKV6_OK;
     const long long need = static_cast<long long>(T) * H * N;
     if (T > 0) {
-        if (!r || !k || !v || !x || !out) return WKV6_ERR_NULL;
+        if (!r || !k || !v || !x || !out || (finch_c2 && !uprime)) return WKV6_ERR_NULL;
         if (batch_stride < need) return WKV6_ERR_SHAPE;
-        if (misaligned(r) || misaligned(k) || misaligned(v) || misaligned(x) || misaligned(out))
+        if (misaligned(r) || misaligned(k) || misaligned(v) || misaligned(x) || misaligned(out) ||
+            misaligned(uprime))
             return WKV6_ERR_ALIGN;
         if (batch_stride % 8 != 0) return WKV6_ERR_ALIGN;
     }
@@ -32,6 +35,7 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     wkv6::Args a;
     a.B = B; a.T = T; a.H = H;
     a.r = r; a.k = k; a.v = v; a.x = x; a.u = u;
+    a.uprime = finch_c2 ? uprime : nullptr;
     a.state_in = state_in; a.out = out; a.state_out = state_out;
     a.batch_stride = batch_stride;
     a.segs = 1; a.T_last = T; a.seg_stride = 0; a.decay_out = nullptr;
@@ -74,6 +78,30 @@ int wkv6_prefill_bf16_strided(int B, int T, int H, int N, const void* r, const v
                out_dtype == WKV6_DTYPE_F32, Path::kChunked, stream);
 }
 
+int wkv6_finch_c2_prefill_bf16(int B, int T, int H, int N, const void* r, const void* kbar,
+                               const void* v, const void* x, const void* uprime,
+                               const float* state_in, void* out, float* state_out, void* stream) {
+    return run(B, T, H, N, r, kbar, v, x, nullptr, state_in, out, state_out,
+               static_cast<long long>(T) * H * N, true, false, Path::kChunked, stream, uprime, true);
+}
+
+int wkv6_finch_c2_prefill_bf16_f32out(int B, int T, int H, int N, const void* r, const void* kbar,
+                                      const void* v, const void* x, const void* uprime,
+                                      const float* state_in, float* out, float* state_out,
+                                      void* stream) {
+    return run(B, T, H, N, r, kbar, v, x, nullptr, state_in, out, state_out,
+               static_cast<long long>(T) * H * N, true, true, Path::kChunked, stream, uprime, true);
+}
+
+int wkv6_finch_c2_prefill_bf16_strided(int B, int T, int H, int N, const void* r, const void* kbar,
+                                       const void* v, const void* x, const void* uprime,
+                                       const float* state_in, void* out, float* state_out,
+                                       long long batch_stride, int out_dtype, void* stream) {
+    if (out_dtype != WKV6_DTYPE_BF16 && out_dtype != WKV6_DTYPE_F32) return WKV6_ERR_UNSUPPORTED;
+    return run(B, T, H, N, r, kbar, v, x, nullptr, state_in, out, state_out, batch_stride, true,
+               out_dtype == WKV6_DTYPE_F32, Path::kChunked, stream, uprime, true);
+}
+
 int wkv6_prefill_f32(int B, int T, int H, int N, const float* r, const float* k, const float* v,
                      const float* x, const float* u, const float* state_in, float* out,
                      float* state_out, void* stream) {
@@ -101,7 +129,7 @@ const char* wkv6_status_string(int status) {
     }
 }
 
-int wkv6_version(void) { return 100; }
+int wkv6_version(void) { return 200; }
 
 }  // extern "C"
 
@@ -175,6 +203,7 @@ int wkv6_prefill_bf16_split(int B, int T, int H, int N, const void* r, const voi
     wkv6::Args a;
     a.B = B; a.T = p.seg_len; a.H = H;
     a.r = r; a.k = k; a.v = v; a.x = x; a.u = u;
+    a.uprime = nullptr;
     a.batch_stride = static_cast<long long>(T) * H * N;
     a.segs = p.segs; a.T_last = p.last_len;
     a.seg_stride = static_cast<long long>(p.seg_len) * H * N;

@@ -23,16 +23,20 @@
 // a second half); one MFMA per level and 16x16 block followed by a select assembles the
 // score matrix.
 //
-// Work split inside the workgroup (12 wavefronts, 3 per SIMD), one barrier per chunk:
-//   waves 0..3 / 4..7  two PRODUCER groups; group g owns the chunks of parity g and its own
-//               set of LDS tiles.  A group alternates between phase T (take the other token
-//               groups' decay totals, write every fp16 operand tile of its chunk) and phase S
-//               (score MFMAs of that chunk, finished output rows of an earlier chunk to HBM,
-//               decays of its next chunk, HBM loads of the one after).  While one group is in
-//               T the other is in S, so vector-ALU, LDS and matrix-core work overlap.
-//   waves 8..11 CONSUMERS: each owns 16 value columns of the state and runs the three
+// Work split inside the workgroup (16 wavefronts, 4 per SIMD), one barrier per window:
+//   waves 0..11  three PRODUCER groups of four waves; group g owns the chunks c = g (mod 3) and
+//               spends three windows on each: D (decays, products inside 4-token groups, HBM
+//               loads six chunks ahead), T (multipliers from all groups' totals, every fp16
+//               operand tile), S (score MFMAs, finished output rows of chunk c-2 to HBM).  The
+//               groups run one window apart, so every window has one group in each phase and
+//               vector-ALU, LDS and matrix-core work of different chunks overlap.
+//   waves 12..15 CONSUMERS: each owns 16 value columns of the state and runs the three
 //               state-dependent contractions, the only sequential chain of the method.
-// In window n: T(chunk n), S(chunk n-1), consumers' state chain on chunk n-1 and A.V on n-2.
+// In window n: D(chunk n), T(n-1), S(n-2), consumers' state chain on chunk n-2 and A.V on n-3.
+// LDS buffers (tiles, scores, decay totals, output staging) are indexed by chunk parity.
+//
+// Finch-C2 form (template flag): the key is multiplied by (1 - w) in phase D, there is no bonus
+// tile or bonus MFMA, and the second value u' is added to the fp32-staged rows before the store.
 //
 // LDS tiles are [token][channel] fp16 with a 160-byte row stride, the stride at which the
 // 16-byte row reads of MFMA operands run at the full rate of the gfx950 LDS; operands whose
@@ -47,6 +51,7 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int kChunk = 32;                 // tokens per chunk
 constexpr int kProducerGroups = 3;         // 4 waves each
@@ -56,7 +61,7 @@ constexpr int kTile = kChunk * kRow;       // one [32 tokens][64 channels] tile
 constexpr int kORowF32 = 68;               // output staging row stride, fp32 mode (floats)
 constexpr int kORowBf16 = 72;              // output staging row stride, bf16 mode (halfs)
 
-// LDS map (bytes).  Everything up to kBuf exists twice, once per producer group / chunk parity.
+// LDS map (bytes).  Everything up to kBuf exists twice, once per chunk parity.
 enum : int {
     kZ16 = 0 * kTile,
     kZ8 = 1 * kTile,
@@ -175,8 +180,8 @@ __device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int t0, con
     }
 }
 
-// What a producer thread carries from phase S (where it digests the raw inputs of its next
-// chunk) to phase T (where the other groups' decay totals are known and the tiles are written).
+// What a producer thread carries from phase D (where it digests the raw inputs of its chunk)
+// to phase T (where the other groups' decay totals are known and the tiles are written).
 struct Prep {
     unsigned z2[4], rh[4], kh[4], ru[4], vt[4];           // finished fp16 pairs, one per token
     unsigned rp[4];            // r * prefix product inside the group, fp16 pair (2 channels)
@@ -184,13 +189,14 @@ struct Prep {
 };
 
 // ------------------------------------------------------------------------------------------
-// Producer waves: group pg (0/1) = chunk parity, wq = wave inside the group
+// Producer waves: group pg (0..2) = chunk index mod 3, wq = wave inside the group
 // ------------------------------------------------------------------------------------------
-template <int kMode>
+template <int kMode, bool kC2>
 __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, int pg, int wq, int h,
                                          long long unit_base, long long tok_stride, int T, int nchunks) {
     constexpr bool kOutF32 = kMode == 1;
     constexpr bool kStateOnly = kMode == 2;
+    constexpr bool kStageF32 = kOutF32 || kC2;   // staging precision of the finished rows
     const int lane = tid & 63;
     const int gtid = tid & 255;              // thread inside the group
     const int cp = lane & 31;                // channel pair: channels 2cp, 2cp+1
@@ -202,8 +208,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     const int l16 = lane & 15;
     const int g4 = lane >> 4;
 
-    const float u0 = a.u[h * kHeadSize + 2 * cp];
-    const float u1 = a.u[h * kHeadSize + 2 * cp + 1];
+    const float u0 = kC2 ? 0.f : a.u[h * kHeadSize + 2 * cp];
+    const float u1 = kC2 ? 0.f : a.u[h * kHeadSize + 2 * cp + 1];
 
     Streams st;
     st.r = static_cast<const char*>(a.r) + unit_base * 2;
@@ -235,7 +241,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     Raw raw_a, raw_b;      // raw inputs of this group's next two chunks (in flight or landed)
     Prep pr;
 
-    // Phase S, part 2.  Digest the raw inputs in `cur` (chunk c): decays, their products inside
+    // Phase D.  Digest the raw inputs in `cur` (chunk c): decays, their products inside
     // the thread's 4-token group (published in G), and every operand that needs nothing else.
     auto digest = [&](int c, Raw& cur) {
         char* lds = lds_all + (c & 1) * kBuf;
@@ -264,6 +270,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             for (int s = 0; s < 4; ++s) {
                 r4[ch][s] = ch ? bf16_hi(cur.r[s]) : bf16_lo(cur.r[s]);
                 k4[ch][s] = ch ? bf16_hi(cur.k[s]) : bf16_lo(cur.k[s]);
+                if constexpr (kC2) k4[ch][s] *= 1.f - w[ch][s];      // k = kbar (1 - w)
             }
             rp[ch][0] = r4[ch][0];
             rp[ch][1] = r4[ch][1] * w[ch][0];
@@ -281,7 +288,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             pr.ks[s] = pack_h2(ks[0][s], ks[1][s]);
             pr.rh[s] = pack_h2(r4[0][s], r4[1][s]);
             pr.kh[s] = pack_h2(k4[0][s], k4[1][s]);
-            pr.ru[s] = pack_h2(r4[0][s] * u0, r4[1][s] * u1);
+            if constexpr (!kC2) pr.ru[s] = pack_h2(r4[0][s] * u0, r4[1][s] * u1);
             pr.vt[s] = pack_h2(bf16_lo(cur.v[s]), bf16_hi(cur.v[s]));
         }
         // level 2: tokens 0,1 of the group are keys, 2,3 queries
@@ -346,7 +353,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             lds_write_u32(lds, kZ2 + nat, pr.z2[s]);
             lds_write_u32(lds, kRH + nat, pr.rh[s]);
             lds_write_u32(lds, kKH + nat, pr.kh[s]);
-            lds_write_u32(lds, kRU + nat, pr.ru[s]);
+            if constexpr (!kC2) lds_write_u32(lds, kRU + nat, pr.ru[s]);
             lds_write_u32(lds, kVT + nat, pr.vt[s]);
             lds_write_u32(lds, kRT + row + rt_col * 2, mul_h2(pr.rp[s], h_rt));
             lds_write_u32(lds, kKT + nat, mul_h2(pr.ks[s], h_kt));
@@ -355,7 +362,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         }
     };
 
-    // Phase S, part 1.  Scores of this group's chunk; the contraction over the 64 channels is
+    // Phase S, part 1.  Scores of chunk c; the contraction over the 64 channels is
     // split in two halves (kk), each wave writes its partial scores to tile A0 or A1 and the
     // consumers add the two products.  Wave wq: diagonal block wq&1, channel half wq>>1; the
     // waves with an even wq also take the level-16 block (t-block 1, i-block 0).
@@ -370,13 +377,13 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         const half8 z2 = lds_read_h8(lds, kZ2 + rowq);
         const half8 rh = lds_read_h8(lds, kRH + rowq);
         const half8 kh = lds_read_h8(lds, kKH + rowq);
-        const half8 ru = lds_read_h8(lds, kRU + rowq);
         const float4v zero{0.f, 0.f, 0.f, 0.f};
         const float4v acc8 = mfma(z8, z8, zero);
         const float4v acc4 = mfma(z4, z4, zero);
         const float4v acc2 = mfma(z2, z2, zero);
         const float4v acc1 = mfma(kh, rh, zero);
-        const float4v accb = mfma(kh, ru, zero);
+        float4v accb = zero;                        // bonus on the diagonal; none in Finch-C2
+        if constexpr (!kC2) accb = mfma(kh, lds_read_h8(lds, kRU + rowq), zero);
         float sel[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -399,32 +406,60 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     };
 
     // Phase S, part 2.  Finished output rows of chunk c (staged by the consumers): full
-    // 128-byte (bf16) rows to HBM, 8 threads per row.
+    // 128-byte (bf16) rows to HBM, 8 threads per row.  Finch-C2: the rows are staged in fp32 and
+    // the second value u' of the same 8 channels (16 bytes, loaded two windows earlier) is added
+    // before the single rounding of the output.
+    const int srow = gtid >> 3;                  // token row inside the chunk this thread stores
+    const int scol = 8 * (gtid & 7);             // first of its 8 channels
+    [[maybe_unused]] uint4v up_raw = {0u, 0u, 0u, 0u};
+    [[maybe_unused]] const int up_voff = static_cast<int>(srow * st.row_bytes + scol * 2);
+    [[maybe_unused]] const char* up_base = kC2 ? static_cast<const char*>(a.uprime) + unit_base * 2 : nullptr;
+    auto load_uprime = [&](int c) {
+        if constexpr (kC2 && !kStateOnly) {
+            const int cc = c < 0 ? 0 : c;                                  // unconditional: exact wait counts
+            const long long off = static_cast<long long>(cc) * kChunk * st.row_bytes;
+            up_raw = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(
+                                                    chunk_rsrc(up_base, off, st.span_bytes), up_voff, 0, 0));
+        }
+    };
     auto store_rows = [&](int c) {
         const char* lds = lds_all + (c & 1) * kBuf;
-        const int row = gtid >> 3;
-        const int col = 8 * (gtid & 7);
-        const int t = c * kChunk + row;
+        const int t = c * kChunk + srow;
         if (t < T) {
-            const long long e = unit_base + static_cast<long long>(t) * tok_stride + col;
-            if constexpr (kOutF32) {
-                const float4* src = reinterpret_cast<const float4*>(lds + kO + (row * kORowF32 + col) * 4);
-                float4* dst = reinterpret_cast<float4*>(static_cast<float*>(a.out) + e);
-                const float4 q0 = src[0], q1 = src[1];
-                dst[0] = q0;
-                dst[1] = q1;
+            const long long e = unit_base + static_cast<long long>(t) * tok_stride + scol;
+            if constexpr (kStageF32) {
+                const float4* src = reinterpret_cast<const float4*>(lds + kO + (srow * kORowF32 + scol) * 4);
+                float4 q0 = src[0], q1 = src[1];
+                if constexpr (kC2) {
+                    q0.x += bf16_lo(up_raw[0]); q0.y += bf16_hi(up_raw[0]);
+                    q0.z += bf16_lo(up_raw[1]); q0.w += bf16_hi(up_raw[1]);
+                    q1.x += bf16_lo(up_raw[2]); q1.y += bf16_hi(up_raw[2]);
+                    q1.z += bf16_lo(up_raw[3]); q1.w += bf16_hi(up_raw[3]);
+                }
+                if constexpr (kOutF32) {
+                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(a.out) + e);
+                    dst[0] = q0;
+                    dst[1] = q1;
+                } else {
+                    uint4 q;
+                    q.x = bf16_bits(q0.x) | (static_cast<unsigned>(bf16_bits(q0.y)) << 16);
+                    q.y = bf16_bits(q0.z) | (static_cast<unsigned>(bf16_bits(q0.w)) << 16);
+                    q.z = bf16_bits(q1.x) | (static_cast<unsigned>(bf16_bits(q1.y)) << 16);
+                    q.w = bf16_bits(q1.z) | (static_cast<unsigned>(bf16_bits(q1.w)) << 16);
+                    *reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.out) + e) = q;
+                }
             } else {
-                const uint4 q = *reinterpret_cast<const uint4*>(lds + kO + (row * kORowBf16 + col) * 2);
+                const uint4 q = *reinterpret_cast<const uint4*>(lds + kO + (srow * kORowBf16 + scol) * 2);
                 *reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.out) + e) = q;
             }
         }
     };
 
     // A group spends three consecutive windows on each of its chunks c = pg, pg+3, ...:
-    //   window c    phase D: decays and group products of chunk c from the raw registers, then
-    //               the HBM loads of the group's next chunk (c+3) into the same registers; they
-    //               stay in flight for three windows.  Issued unconditionally: past the end the
-    //               descriptor is empty and the loads return zeros without touching memory.
+    //   window c    phase D: decays and group products of chunk c from one of two raw register
+    //               sets, then the HBM loads of the group's chunk after next (c+6) into the same
+    //               set; they stay in flight for six windows.  Issued unconditionally: past the
+    //               end the descriptor is empty and the loads return zeros without touching memory.
     //   window c+1  phase T: multipliers from all groups' decay totals, every operand tile.
     //   window c+2  phase S: score MFMAs, and the finished output rows of chunk c-2.
     // The three groups are one window apart, so every window sees one group in each phase
@@ -434,6 +469,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // refilled with the group's chunk after next (six chunks ahead) right after the digest
     auto cycle = [&](int c, Raw& buf) {
         if (c < nchunks) digest(c, buf);
+        load_uprime(c - 2);                       // older than the chunk loads: waited for first
         load_rows<kStateOnly>(buf, st, (c + 6) * kChunk, voff);
         __syncthreads();                                                        // window barrier
         if (c < nchunks) write_tiles(c);
@@ -470,7 +506,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 // ------------------------------------------------------------------------------------------
 // Consumer waves
 // ------------------------------------------------------------------------------------------
-template <int kMode>
+template <int kMode, bool kC2>
 __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane, int cw, int unit, int nchunks) {
     constexpr bool kOutF32 = kMode == 1;
     constexpr bool kStateOnly = kMode == 2;
@@ -517,7 +553,7 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int row = 16 * tq + 4 * g4 + e;
-                    if constexpr (kOutF32)
+                    if constexpr (kOutF32 || kC2)
                         *reinterpret_cast<float*>(lds + kO + (row * kORowF32 + j) * 4) = o[tq][e];
                     else
                         *reinterpret_cast<unsigned short*>(lds + kO + (row * kORowBf16 + j) * 2) = bf16_bits(o[tq][e]);
@@ -573,7 +609,7 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
     if (a.decay_out && cw == 0) a.decay_out[static_cast<long long>(unit) * kHeadSize + lane] = dtot;
 }
 
-template <int kMode>
+template <int kMode, bool kC2>
 __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
@@ -590,9 +626,9 @@ __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
     const int T = (seg == a.segs - 1) ? a.T_last : a.T;
     const int nchunks = (T + kChunk - 1) / kChunk;
     if (wid < 4 * kProducerGroups)
-        producer<kMode>(a, lds, tid, wid >> 2, wid & 3, h, unit_base, tok_stride, T, nchunks);
+        producer<kMode, kC2>(a, lds, tid, wid >> 2, wid & 3, h, unit_base, tok_stride, T, nchunks);
     else
-        consumer<kMode>(a, lds, tid & 63, wid - 4 * kProducerGroups, unit, nchunks);
+        consumer<kMode, kC2>(a, lds, tid & 63, wid - 4 * kProducerGroups, unit, nchunks);
 }
 
 // Sequential fold over the segments of one (batch, head): 256 threads x 16 state entries.
@@ -632,23 +668,24 @@ __global__ __launch_bounds__(256) void combine_kernel(int H, int segs, const flo
     }
 }
 
-template <int kMode>
+template <int kMode, bool kC2>
 hipError_t launch_mode(const Args& a, hipStream_t stream) {
     const dim3 grid(static_cast<unsigned>(a.B) * static_cast<unsigned>(a.segs) * static_cast<unsigned>(a.H));
-    const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunked_kernel<kMode>),
+    const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunked_kernel<kMode, kC2>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(chunked_kernel<kMode>, grid, dim3(kThreads), kLdsBytes, stream, a);
+    hipLaunchKernelGGL((chunked_kernel<kMode, kC2>), grid, dim3(kThreads), kLdsBytes, stream, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream) {
+    const bool c2 = a.uprime != nullptr;             // Finch-C2 form: second value instead of bonus
     switch (mode) {
-        case ChunkedMode::kBf16Out: return launch_mode<0>(a, stream);
-        case ChunkedMode::kF32Out: return launch_mode<1>(a, stream);
-        default: return launch_mode<2>(a, stream);
+        case ChunkedMode::kBf16Out: return c2 ? launch_mode<0, true>(a, stream) : launch_mode<0, false>(a, stream);
+        case ChunkedMode::kF32Out: return c2 ? launch_mode<1, true>(a, stream) : launch_mode<1, false>(a, stream);
+        default: return launch_mode<2, false>(a, stream);
     }
 }
 

@@ -12,7 +12,10 @@ struct Args {
     const void* k;
     const void* v;
     const void* x;
-    const float* u;
+    const float* u;           // Finch bonus [H][N]; unused when uprime is set
+    const void* uprime;       // nullptr: Finch form.  Otherwise the Finch-C2 form: k is the key before its
+                              // (1 - w) factor, no bonus, and this second value [B][T][H][N] (bf16, laid out
+                              // like out) is added to the read-out
     const float* state_in;    // may be nullptr (zero state)
     void* out;
     float* state_out;         // may be nullptr (not written)

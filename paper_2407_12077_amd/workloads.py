@@ -118,3 +118,15 @@ def make_inputs(cfg, seed=None):
     elif cfg.dtype != "f32":
         raise ValueError(cfg.dtype)
     return {"r": r, "k": k, "v": v, "x": x, "u": u, "state_in": state_in}
+
+
+def make_uprime(cfg, seed=None):
+    """Second value u' of the Finch-C2 form for ``cfg``: [B, T, H, N], N(0,1)/sqrt(N) like v
+    (it is a value-projection output plus a low-rank term), rounded to ``cfg.dtype``.  Drawn from
+    its own generator, ``PCG64(seed + 1000)``, so the draws of ``make_inputs`` do not move."""
+    if seed is None:
+        seed = BASE_SEED + cfg.index
+    rng = np.random.Generator(np.random.PCG64(seed + 1000))
+    a = rng.standard_normal((cfg.B, cfg.T, cfg.H, cfg.N), dtype=np.float32)
+    a *= np.float32(1.0 / np.sqrt(cfg.N))
+    return round_to_bf16(a) if cfg.dtype == "bf16" else a

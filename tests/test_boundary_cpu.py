@@ -60,6 +60,20 @@ def test_validation_happens_before_any_launch(name):
     assert f(70000, 8, 70000, 64, A, A, A, A, A, None, A, A, None) == 2              # grid overflow
 
 
+@pytest.mark.parametrize("name", ["wkv6_finch_c2_prefill_bf16", "wkv6_finch_c2_prefill_bf16_f32out"])
+def test_finch_c2_validation_happens_before_any_launch(name):
+    f = _raw(name)
+    assert f(1, 8, 2, 32, A, A, A, A, A, None, A, A, None) == 3          # N != 64
+    assert f(1, -8, 2, 64, A, A, A, A, A, None, A, A, None) == 2
+    assert f(1, 8, 2, 64, A, None, A, A, A, None, A, A, None) == 1       # kbar
+    assert f(1, 8, 2, 64, A, A, A, A, None, None, A, A, None) == 1       # uprime
+    assert f(1, 8, 2, 64, A, A, A, A, P(0x1002), None, A, A, None) == 5  # uprime alignment
+    assert f(0, 8, 2, 64, None, None, None, None, None, None, None, None, None) == 0
+    g = _raw("wkv6_finch_c2_prefill_bf16_strided")
+    assert g(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64 - 8, 1, None) == 2
+    assert g(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64, 7, None) == 3
+
+
 def test_strided_entry_validation():
     f = _raw("wkv6_prefill_bf16_strided")
     assert f(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64 - 8, 1, None) == 2   # stride < T*H*N
