@@ -44,6 +44,8 @@
 // ds_read_b64_tr_b16 instead of keeping transposed copies.
 #include "wkv6_launch.h"
 
+#include <type_traits>
+
 namespace wkv6 {
 namespace {
 
@@ -67,15 +69,14 @@ enum : int {
     kZ8 = 1 * kTile,
     kZ4 = 2 * kTile,
     kZ2 = 3 * kTile,
-    kRH = 4 * kTile,       // r as fp16 (level 1 queries)
-    kKH = 5 * kTile,       // k as fp16 (level 1 and bonus keys)
-    kRU = 6 * kTile,       // r*u       (bonus queries)
-    kRT = 7 * kTile,       // r * W(t,-1), channel order permuted to match the state registers
-    kKT = 8 * kTile,       // k * W(32,i)
-    kVT = 9 * kTile,       // v as fp16
-    kA0 = 10 * kTile,      // scores A[t][i], contraction over channels 0..31
-    kA1 = 11 * kTile,      // scores A[t][i], contraction over channels 32..63
-    kG = 12 * kTile,                       // per 4-token group decay products [8][64] fp32
+    kQ1 = 4 * kTile,       // level 1 and bonus, query side: r (odd tokens), r*u (even tokens)
+    kK1 = 5 * kTile,       // level 1 and bonus, key side:   k (even tokens), k*u (odd tokens)
+    kRT = 6 * kTile,       // r * W(t,-1), channel order permuted to match the state registers
+    kKT = 7 * kTile,       // k * W(32,i)
+    kVT = 8 * kTile,       // v as fp16
+    kA0 = 9 * kTile,       // scores A[t][i], contraction over channels 0..31
+    kA1 = 10 * kTile,      // scores A[t][i], contraction over channels 32..63
+    kG = 11 * kTile,                       // per 4-token group decay products [8][64] fp32
     kD = kG + 8 * 64 * 4,                  // whole-chunk decay product [64] fp32
     kO = kD + 64 * 4,                      // output staging [32 tokens][64]
     kBuf = (kO + kChunk * kORowF32 * 4 + 1023) / 1024 * 1024,
@@ -183,7 +184,7 @@ __device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int t0, con
 // What a producer thread carries from phase D (where it digests the raw inputs of its chunk)
 // to phase T (where the other groups' decay totals are known and the tiles are written).
 struct Prep {
-    unsigned z2[4], rh[4], kh[4], ru[4], vt[4];           // finished fp16 pairs, one per token
+    unsigned z2[4], q1[4], k1[4], vt[4];                  // finished fp16 pairs, one per token
     unsigned rp[4];            // r * prefix product inside the group, fp16 pair (2 channels)
     unsigned ks[4];            // k * suffix product inside the group, fp16 pair
 };
@@ -203,13 +204,11 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     const int hl = lane >> 5;
     const int g8 = 2 * wq + hl;              // 4-token group 0..7 inside the chunk
     const bool q4 = hl != 0;                 // query side at level 4 (per lane half)
-    const bool q8 = (wq & 1) != 0;           //               level 8  (wave-uniform)
-    const bool q16 = (wq & 2) != 0;          //               level 16 (wave-uniform)
     const int l16 = lane & 15;
     const int g4 = lane >> 4;
 
-    const float u0 = kC2 ? 0.f : a.u[h * kHeadSize + 2 * cp];
-    const float u1 = kC2 ? 0.f : a.u[h * kHeadSize + 2 * cp + 1];
+    // the bonus u of this channel pair as an fp16 pair (Finch form only)
+    const unsigned hu = kC2 ? 0u : pack_h2(a.u[h * kHeadSize + 2 * cp], a.u[h * kHeadSize + 2 * cp + 1]);
 
     Streams st;
     st.r = static_cast<const char*>(a.r) + unit_base * 2;
@@ -258,48 +257,61 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             w[0][s] = decay_of(bf16_lo(cur.x[s]));
             w[1][s] = decay_of(bf16_hi(cur.x[s]));
         }
-        float r4[2][4], k4[2][4], rp[2][4], ks[2][4], gtot[2];
+        // products of decays inside the group, fp32: prefix of token 2 and 3, suffix of token 1
+        // and 0, and the group total
+        float p2[2], p3[2], s1[2], s0[2];
 #pragma unroll
         for (int ch = 0; ch < 2; ++ch) {
-            const float p2 = w[ch][0] * w[ch][1];            // prefix of token 2
-            const float p3 = p2 * w[ch][2];                  // prefix of token 3
-            const float s1 = w[ch][2] * w[ch][3];            // suffix of token 1
-            const float s0 = w[ch][1] * s1;                  // suffix of token 0
-            gtot[ch] = p3 * w[ch][3];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                r4[ch][s] = ch ? bf16_hi(cur.r[s]) : bf16_lo(cur.r[s]);
-                k4[ch][s] = ch ? bf16_hi(cur.k[s]) : bf16_lo(cur.k[s]);
-                if constexpr (kC2) k4[ch][s] *= 1.f - w[ch][s];      // k = kbar (1 - w)
-            }
-            rp[ch][0] = r4[ch][0];
-            rp[ch][1] = r4[ch][1] * w[ch][0];
-            rp[ch][2] = r4[ch][2] * p2;
-            rp[ch][3] = r4[ch][3] * p3;
-            ks[ch][0] = k4[ch][0] * s0;
-            ks[ch][1] = k4[ch][1] * s1;
-            ks[ch][2] = k4[ch][2] * w[ch][3];
-            ks[ch][3] = k4[ch][3];
+            p2[ch] = w[ch][0] * w[ch][1];
+            p3[ch] = p2[ch] * w[ch][2];
+            s1[ch] = w[ch][2] * w[ch][3];
+            s0[ch] = w[ch][1] * s1[ch];
         }
-        *reinterpret_cast<float2*>(lds + kG + (g8 * 64 + 2 * cp) * 4) = make_float2(gtot[0], gtot[1]);
+        *reinterpret_cast<float2*>(lds + kG + (g8 * 64 + 2 * cp) * 4) =
+            make_float2(p3[0] * w[0][3], p3[1] * w[1][3]);
+        // r, k, v as fp16 channel pairs (exact: bf16 has fewer significant bits); every scaled
+        // operand is one packed fp16 multiply with a multiplier rounded to fp16
+        unsigned rh[4], kh[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            pr.rp[s] = pack_h2(rp[0][s], rp[1][s]);
-            pr.ks[s] = pack_h2(ks[0][s], ks[1][s]);
-            pr.rh[s] = pack_h2(r4[0][s], r4[1][s]);
-            pr.kh[s] = pack_h2(k4[0][s], k4[1][s]);
-            if constexpr (!kC2) pr.ru[s] = pack_h2(r4[0][s] * u0, r4[1][s] * u1);
+            rh[s] = pack_h2(bf16_lo(cur.r[s]), bf16_hi(cur.r[s]));
+            if constexpr (kC2)      // Finch-C2: k = kbar (1 - w), the factor applied in fp32
+                kh[s] = pack_h2(bf16_lo(cur.k[s]) * (1.f - w[0][s]), bf16_hi(cur.k[s]) * (1.f - w[1][s]));
+            else
+                kh[s] = pack_h2(bf16_lo(cur.k[s]), bf16_hi(cur.k[s]));
             pr.vt[s] = pack_h2(bf16_lo(cur.v[s]), bf16_hi(cur.v[s]));
         }
+        pr.rp[0] = rh[0];
+        pr.rp[1] = mul_h2(rh[1], pack_h2(w[0][0], w[1][0]));
+        pr.rp[2] = mul_h2(rh[2], pack_h2(p2[0], p2[1]));
+        pr.rp[3] = mul_h2(rh[3], pack_h2(p3[0], p3[1]));
+        const unsigned hw3 = pack_h2(w[0][3], w[1][3]);
+        pr.ks[0] = mul_h2(kh[0], pack_h2(s0[0], s0[1]));
+        pr.ks[1] = mul_h2(kh[1], pack_h2(s1[0], s1[1]));
+        pr.ks[2] = mul_h2(kh[2], hw3);
+        pr.ks[3] = kh[3];
         // level 2: tokens 0,1 of the group are keys, 2,3 queries
-        pr.z2[0] = pack_h2(k4[0][0] * w[0][1], k4[1][0] * w[1][1]);
-        pr.z2[1] = pr.kh[1];
-        pr.z2[2] = pr.rh[2];
-        pr.z2[3] = pack_h2(r4[0][3] * w[0][2], r4[1][3] * w[1][2]);
+        pr.z2[0] = mul_h2(kh[0], pack_h2(w[0][1], w[1][1]));
+        pr.z2[1] = kh[1];
+        pr.z2[2] = rh[2];
+        pr.z2[3] = mul_h2(rh[3], pack_h2(w[0][2], w[1][2]));
+        // level 1 (odd token t reads even token t-1, no decay between them) and the bonus on the
+        // diagonal share one query tile and one key tile: u rides on the query for even tokens
+        // and on the key for odd tokens, so the diagonal gets r.u.k and the pair gets plain r.k
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            pr.q1[s] = (kC2 || (s & 1)) ? rh[s] : mul_h2(rh[s], hu);
+            pr.k1[s] = (kC2 || !(s & 1)) ? kh[s] : mul_h2(kh[s], hu);
+        }
     };
 
-    // Phase T: multipliers from the other groups' decay totals, then every operand tile.
-    auto write_tiles = [&](int c) {
+    // Phase T: multipliers from the other groups' decay totals, then every operand tile.  The
+    // body is instantiated per wave position kWq so that the level-8 and level-16 roles (key or
+    // query side) and the neighbouring group products are compile-time choices.
+    auto write_tiles_at = [&](auto wq_const, int c) {
+        constexpr int kWq = decltype(wq_const)::value;
+        constexpr bool kQ8 = (kWq & 1) != 0;     // query side at level 8
+        constexpr bool kQ16 = (kWq & 2) != 0;    // query side at level 16
         char* lds = lds_all + (c & 1) * kBuf;
         float m_rt[2], m_kt[2], m16[2], m8[2];
         float2 own[8];
@@ -311,54 +323,62 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             float o[8];
 #pragma unroll
             for (int g = 0; g < 8; ++g) o[g] = ch ? own[g].y : own[g].x;
-            // pl / ph: decays of the group pairs before / after this wave's pair (wq is uniform);
+            // pl / ph: decays of the group pairs before / after this wave's pair;
             // f16: this wave's share of the level-16 multiplier
-            float pl, ph, f16, mate;
-            switch (wq) {
-                case 0:  pl = 1.f; ph = (o[2] * o[3]) * ((o[4] * o[5]) * (o[6] * o[7])); f16 = o[2] * o[3];
-                         mate = hl ? o[0] : o[1]; break;
-                case 1:  pl = o[0] * o[1]; ph = (o[4] * o[5]) * (o[6] * o[7]); f16 = 1.f;
-                         mate = hl ? o[2] : o[3]; break;
-                case 2:  pl = (o[0] * o[1]) * (o[2] * o[3]); ph = o[6] * o[7]; f16 = 1.f;
-                         mate = hl ? o[4] : o[5]; break;
-                default: pl = ((o[0] * o[1]) * (o[2] * o[3])) * (o[4] * o[5]); ph = 1.f; f16 = o[4] * o[5];
-                         mate = hl ? o[6] : o[7]; break;
-            }
-            // `mate` is the other group of this wave's pair: it lies before the odd group (hl=1)
-            // and after the even one (hl=0)
-            const float before = hl ? mate : 1.f;
-            const float after = hl ? 1.f : mate;
+            float pl, ph, f16;
+            if constexpr (kWq == 0) { pl = 1.f; ph = (o[2] * o[3]) * ((o[4] * o[5]) * (o[6] * o[7])); f16 = o[2] * o[3]; }
+            else if constexpr (kWq == 1) { pl = o[0] * o[1]; ph = (o[4] * o[5]) * (o[6] * o[7]); f16 = 1.f; }
+            else if constexpr (kWq == 2) { pl = (o[0] * o[1]) * (o[2] * o[3]); ph = o[6] * o[7]; f16 = 1.f; }
+            else { pl = ((o[0] * o[1]) * (o[2] * o[3])) * (o[4] * o[5]); ph = 1.f; f16 = o[4] * o[5]; }
+            // the other group of this wave's pair lies before the odd group (hl=1) and after
+            // the even one (hl=0)
+            const float before = hl ? o[2 * kWq] : 1.f;
+            const float after = hl ? 1.f : o[2 * kWq + 1];
             m_rt[ch] = pl * before;            // decays of the chunk's tokens before this group
             m_kt[ch] = after * ph;             // decays of the chunk's tokens after this group
-            m16[ch] = q16 ? f16 * before : after * f16;   // level 16: inside the 16-token half
-            m8[ch] = q8 ? before : after;                 // level 8: inside the 8-token block
-            if (g8 == 0) *reinterpret_cast<float*>(lds + kD + (2 * cp + ch) * 4) = o[0] * m_kt[ch];
+            m16[ch] = kQ16 ? f16 * before : after * f16;   // level 16: inside the 16-token half
+            m8[ch] = kQ8 ? before : after;                 // level 8: inside the 8-token block
+            if constexpr (kWq == 0)
+                if (hl == 0) *reinterpret_cast<float*>(lds + kD + (2 * cp + ch) * 4) = o[0] * m_kt[ch];
         }
         // the multipliers as fp16 channel pairs: one packed multiply per tile entry
         const unsigned h_rt = pack_h2(m_rt[0], m_rt[1]);
         const unsigned h_kt = pack_h2(m_kt[0], m_kt[1]);
         const unsigned h16 = pack_h2(m16[0], m16[1]);
         const unsigned h8 = pack_h2(m8[0], m8[1]);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int row = (4 * g8 + s) * kRow;
-            const int nat = row + 4 * cp;                    // natural channel order
-            if constexpr (kStateOnly) {
-                lds_write_u32(lds, kVT + nat, pr.vt[s]);
-                lds_write_u32(lds, kKT + nat, mul_h2(pr.ks[s], h_kt));
-                continue;
-            }
+        // Writes are grouped by tile, the four tokens of a tile back to back and the one tile with
+        // its own column order last, so that neighbouring writes pair up into two-address LDS
+        // instructions.
+        const int nat0 = 4 * g8 * kRow + 4 * cp;             // token 0 of the group, natural channel order
+        auto put4 = [&](int tile, unsigned v0, unsigned v1, unsigned v2, unsigned v3) {
+            lds_write_u32(lds, tile + nat0, v0);
+            lds_write_u32(lds, tile + nat0 + kRow, v1);
+            lds_write_u32(lds, tile + nat0 + 2 * kRow, v2);
+            lds_write_u32(lds, tile + nat0 + 3 * kRow, v3);
+        };
+        put4(kVT, pr.vt[0], pr.vt[1], pr.vt[2], pr.vt[3]);
+        put4(kKT, mul_h2(pr.ks[0], h_kt), mul_h2(pr.ks[1], h_kt), mul_h2(pr.ks[2], h_kt), mul_h2(pr.ks[3], h_kt));
+        if constexpr (!kStateOnly) {
             // level 4: the even group of an 8-block holds keys, the odd one queries
-            lds_write_u32(lds, kZ4 + nat, q4 ? pr.rp[s] : pr.ks[s]);
-            lds_write_u32(lds, kZ2 + nat, pr.z2[s]);
-            lds_write_u32(lds, kRH + nat, pr.rh[s]);
-            lds_write_u32(lds, kKH + nat, pr.kh[s]);
-            if constexpr (!kC2) lds_write_u32(lds, kRU + nat, pr.ru[s]);
-            lds_write_u32(lds, kVT + nat, pr.vt[s]);
-            lds_write_u32(lds, kRT + row + rt_col * 2, mul_h2(pr.rp[s], h_rt));
-            lds_write_u32(lds, kKT + nat, mul_h2(pr.ks[s], h_kt));
-            lds_write_u32(lds, kZ16 + nat, mul_h2(q16 ? pr.rp[s] : pr.ks[s], h16));
-            lds_write_u32(lds, kZ8 + nat, mul_h2(q8 ? pr.rp[s] : pr.ks[s], h8));
+            put4(kZ4, q4 ? pr.rp[0] : pr.ks[0], q4 ? pr.rp[1] : pr.ks[1], q4 ? pr.rp[2] : pr.ks[2],
+                 q4 ? pr.rp[3] : pr.ks[3]);
+            put4(kZ2, pr.z2[0], pr.z2[1], pr.z2[2], pr.z2[3]);
+            put4(kQ1, pr.q1[0], pr.q1[1], pr.q1[2], pr.q1[3]);
+            put4(kK1, pr.k1[0], pr.k1[1], pr.k1[2], pr.k1[3]);
+            const unsigned* z16 = kQ16 ? pr.rp : pr.ks;
+            const unsigned* z8 = kQ8 ? pr.rp : pr.ks;
+            put4(kZ16, mul_h2(z16[0], h16), mul_h2(z16[1], h16), mul_h2(z16[2], h16), mul_h2(z16[3], h16));
+            put4(kZ8, mul_h2(z8[0], h8), mul_h2(z8[1], h8), mul_h2(z8[2], h8), mul_h2(z8[3], h8));
+            put4(kRT + (rt_col - 2 * cp) * 2, mul_h2(pr.rp[0], h_rt), mul_h2(pr.rp[1], h_rt),
+                 mul_h2(pr.rp[2], h_rt), mul_h2(pr.rp[3], h_rt));
+        }
+    };
+    auto write_tiles = [&](int c) {
+        switch (wq) {                             // wave-uniform
+            case 0: write_tiles_at(std::integral_constant<int, 0>{}, c); break;
+            case 1: write_tiles_at(std::integral_constant<int, 1>{}, c); break;
+            case 2: write_tiles_at(std::integral_constant<int, 2>{}, c); break;
+            default: write_tiles_at(std::integral_constant<int, 3>{}, c); break;
         }
     };
 
@@ -375,23 +395,20 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         const half8 z8 = lds_read_h8(lds, kZ8 + rowq);
         const half8 z4 = lds_read_h8(lds, kZ4 + rowq);
         const half8 z2 = lds_read_h8(lds, kZ2 + rowq);
-        const half8 rh = lds_read_h8(lds, kRH + rowq);
-        const half8 kh = lds_read_h8(lds, kKH + rowq);
+        const half8 q1 = lds_read_h8(lds, kQ1 + rowq);
+        const half8 k1 = lds_read_h8(lds, kK1 + rowq);
         const float4v zero{0.f, 0.f, 0.f, 0.f};
         const float4v acc8 = mfma(z8, z8, zero);
         const float4v acc4 = mfma(z4, z4, zero);
         const float4v acc2 = mfma(z2, z2, zero);
-        const float4v acc1 = mfma(kh, rh, zero);
-        float4v accb = zero;                        // bonus on the diagonal; none in Finch-C2
-        if constexpr (!kC2) accb = mfma(kh, lds_read_h8(lds, kRU + rowq), zero);
+        const float4v acc1 = mfma(k1, q1, zero);     // pairs (odd t, t-1) and, on the diagonal, the bonus
         float sel[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int i = 4 * g4 + e, t = l16;
             const int d = i ^ t;
-            float val = d >= 8 ? acc8[e] : d >= 4 ? acc4[e] : d >= 2 ? acc2[e] : acc1[e];
-            val = (i == t) ? accb[e] : val;
-            sel[e] = (i > t) ? 0.f : val;
+            const float val = d >= 8 ? acc8[e] : d >= 4 ? acc4[e] : d >= 2 ? acc2[e] : acc1[e];
+            sel[e] = (kC2 ? i >= t : i > t) ? 0.f : val;    // Finch-C2 has no diagonal term
         }
         *reinterpret_cast<uint2*>(lds + at + (16 * q + l16) * kRow + (16 * q + 4 * g4) * 2) =
             make_uint2(pack_h2(sel[0], sel[1]), pack_h2(sel[2], sel[3]));
