@@ -39,9 +39,11 @@
  * products of decays (all <= 1), never a reciprocal, so there is no clamp.
  *
  * Value range of the bf16 entry points: the dense contractions run on the
- * matrix cores with fp16 operands and fp32 accumulation; r, k, v and the
- * running state must stay below 65504 in magnitude (larger values saturate to
- * that bound).  The fp32 entry point has no such limit.
+ * matrix cores with fp16 operands and fp32 accumulation; r, k, v, the products
+ * r*u and k*u, the intra-chunk scores and the running state must stay below
+ * 65504 in magnitude (larger values saturate to that bound: results stay
+ * finite but are those of the clamped operands).  The fp32 entry point has no
+ * such limit.
  *
  * Errors: every entry point returns a wkv6_status.  Arguments are validated
  * before anything is enqueued; on a non-zero status nothing was launched,

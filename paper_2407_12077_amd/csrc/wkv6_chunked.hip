@@ -629,6 +629,10 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
 template <int kMode, bool kC2>
 __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    // MODE.FP16_OVFL = 1 (hwreg id 1, bit 23, one bit): fp16 results that overflow, conversions
+    // included, are clamped to +-65504 instead of becoming infinite, so operands beyond the fp16
+    // range saturate as the header promises; true infinities are preserved.
+    __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), 1);
     const int tid = threadIdx.x;
     const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int unit = blockIdx.x;                 // (batch * segs + segment) * H + head

@@ -308,3 +308,25 @@ def test_full_size_config_sampled_units(gpu_device, cfg_index, n_units):
         torch.cuda.synchronize()
         assert max_norm_err(o3.cpu().numpy(), out.cpu().numpy()) <= TOL_BF16
         assert max_norm_err(s3.cpu().numpy(), s_out.cpu().numpy()) <= TOL_BF16
+
+
+def test_operands_beyond_fp16_range_saturate(gpu_device):
+    """The header's value-range clause: on the bf16 entry points operands larger than the fp16
+    maximum saturate to +-65504 (no infinities, no NaNs): the result is that of the oracle run on
+    the clamped inputs."""
+    cfg = scaled(CONFIGS[2], B=1, T=160, H=2)
+    inp = make_inputs(cfg)
+    rng = np.random.default_rng(77)
+    k = inp["k"].copy()
+    hit = rng.random(k.shape) < 0.002
+    k[hit] = np.where(rng.random(hit.sum()) < 0.5, 1.0e5, -3.0e5).astype(np.float32)
+    inp["k"] = round_to_bf16(k)
+    inp["v"] = inp["v"] * np.float32(0.125)        # keeps every state entry inside the fp16 range
+    inp["u"] = np.clip(inp["u"], -1.0, 1.0)        # ... and the bonus-weighted key k*u
+    o, s = run_entry("wkv6_prefill_bf16_f32out", inp)
+    assert np.isfinite(o).all() and np.isfinite(s).all()
+    clamped = dict(inp)
+    clamped["k"] = np.clip(inp["k"], -65504.0, 65504.0)
+    o_ref, s_ref = wkv6_oracle(**clamped)
+    assert 1.0e3 < np.abs(s_ref).max() < 3.0e4
+    assert max_norm_err(o, o_ref) <= TOL_BF16 and max_norm_err(s, s_ref) <= TOL_BF16
