@@ -72,7 +72,7 @@ def main():
     ap.add_argument("--entry", default="wkv6_prefill_bf16",
                     choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent",
                              "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
-                             "wkv6_finch_c2_prefill_bf16_f32out"])
+                             "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_decode_bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 512 MiB device copy (calibrates rocprofv3 byte counters)")
@@ -89,6 +89,12 @@ def main():
         sys.exit("bench.py: no GPU visible")
     wkv.load()                                   # fails loudly if the HIP library is missing
     cfg = CONFIGS[args.config]
+    decode = args.entry == "wkv6_decode_bf16"
+    if decode:
+        # serving shape: one token for each of 1024 sequences with a carried state (config 4's
+        # distributions); 1.07 GB of state traffic per step, well beyond the 256 MB last-level cache
+        from paper_2407_12077_amd.workloads import scaled
+        cfg = scaled(CONFIGS[4], B=1024, T=1, name="decode-step")
     inp = make_inputs(cfg)
     B, T, H, N = cfg.B, cfg.T, cfg.H, cfg.N
 
@@ -102,7 +108,8 @@ def main():
     if finch_c2:
         inp["uprime"] = make_uprime(cfg)
         up = dev(inp["uprime"], torch.bfloat16)
-    out_f32 = args.entry not in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16")
+    out_f32 = args.entry not in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
+                                 "wkv6_decode_bf16")
     out = torch.empty((B, T, H, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
     s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
     fn = getattr(wkv, args.entry)
@@ -117,6 +124,13 @@ def main():
         def step():
             fn(B, T, H, N, r, k, v, x, u, s_in, out, s_out, wkv.WKV6_DTYPE_BF16, segments, ws, ws_bytes,
                stream.cuda_stream)
+    elif decode:
+        segments = 1
+        sq = lambda t: t.view(B, H, N)
+        s_out = s_in                                 # updated in place
+
+        def step():
+            fn(B, H, N, sq(r), sq(k), sq(v), sq(x), u, s_in, sq(out), stream.cuda_stream)
     elif finch_c2:
         segments = 1
 
@@ -166,7 +180,8 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16 tensors; f16 MFMA operands, f32 accumulate and state"
-                 if args.entry != "wkv6_prefill_bf16_recurrent" else "bf16 tensors; f32 vector ALU",
+                 if args.entry not in ("wkv6_prefill_bf16_recurrent", "wkv6_decode_bf16")
+                 else "bf16 tensors; f32 vector ALU, f32 state",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index} ({cfg.name}): B={B} T={T} H={H} N={N}, "
                                f"{'nonzero' if s_in is not None else 'zero'} initial state",

@@ -153,6 +153,36 @@ int wkv6_finch_c2_prefill_bf16_strided(int B, int T, int H, int N,
                                        void *out, float *state_out,
                                        long long batch_stride, int out_dtype, void *stream);
 
+/*
+ * Serving shapes: the same recurrence for one token (decode) or a few tokens (append) per
+ * sequence and many sequences, where the cost is streaming each fp32 state through once
+ * (paper: GoldFinch pre-fill is an RNN pass, so a cache is extended token by token with the
+ * state carried; same equations as above).
+ *
+ * wkv6_decode_bf16: T = 1.  r,k,v,x,out are [B][H][N] bf16; `state` [B][H][N][N] fp32 is read
+ * and updated in place (required, not NULL).  Token-by-token fp32 kernel, no fp16 operands, no
+ * value-range limit.
+ * wkv6_append_bf16: arguments exactly as wkv6_prefill_bf16 (state_in may equal state_out); the
+ * library picks the token-by-token kernel for short T (at most 16 tokens) and the chunked
+ * kernel above that.  Results of the two kernels differ by rounding only, both within the
+ * stated tolerance.
+ * The finch_c2 variants take kbar and uprime instead of k and u (see wkv6_finch_c2_prefill_bf16).
+ */
+int wkv6_decode_bf16(int B, int H, int N,
+                     const void *r, const void *k, const void *v, const void *x,
+                     const float *u, float *state, void *out, void *stream);
+int wkv6_finch_c2_decode_bf16(int B, int H, int N,
+                              const void *r, const void *kbar, const void *v, const void *x,
+                              const void *uprime, float *state, void *out, void *stream);
+int wkv6_append_bf16(int B, int T, int H, int N,
+                     const void *r, const void *k, const void *v, const void *x,
+                     const float *u, const float *state_in,
+                     void *out, float *state_out, void *stream);
+int wkv6_finch_c2_append_bf16(int B, int T, int H, int N,
+                              const void *r, const void *kbar, const void *v, const void *x,
+                              const void *uprime, const float *state_in,
+                              void *out, float *state_out, void *stream);
+
 /* All-fp32 tensors.  Token-by-token kernel with the state in fp32 registers. */
 int wkv6_prefill_f32(int B, int T, int H, int N,
                      const float *r, const float *k, const float *v, const float *x,

@@ -19,7 +19,8 @@ EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_s
            "wkv6_prefill_f32", "wkv6_prefill_bf16_recurrent", "wkv6_prefill_bf16_split",
            "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_finch_c2_prefill_bf16",
            "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_strided",
-           "wkv6_status_string", "wkv6_version")
+           "wkv6_decode_bf16", "wkv6_finch_c2_decode_bf16", "wkv6_append_bf16",
+           "wkv6_finch_c2_append_bf16", "wkv6_status_string", "wkv6_version")
 
 _lib = None
 
@@ -42,7 +43,8 @@ def load():
         common = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_f32",
                      "wkv6_prefill_bf16_recurrent", "wkv6_finch_c2_prefill_bf16",
-                     "wkv6_finch_c2_prefill_bf16_f32out"):
+                     "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_append_bf16",
+                     "wkv6_finch_c2_append_bf16"):
             fn = getattr(lib, name)
             fn.restype = i
             fn.argtypes = common + [vp]
@@ -50,6 +52,10 @@ def load():
         lib.wkv6_prefill_bf16_strided.argtypes = common + [ll, i, vp]
         lib.wkv6_finch_c2_prefill_bf16_strided.restype = i
         lib.wkv6_finch_c2_prefill_bf16_strided.argtypes = common + [ll, i, vp]
+        for name in ("wkv6_decode_bf16", "wkv6_finch_c2_decode_bf16"):
+            fn = getattr(lib, name)
+            fn.restype = i
+            fn.argtypes = [i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.wkv6_prefill_bf16_split.restype = i
         lib.wkv6_prefill_bf16_split.argtypes = common + [i, i, vp, ll, vp]
         lib.wkv6_split_workspace_bytes.restype = ll
@@ -140,6 +146,24 @@ def wkv6_finch_c2_prefill_bf16_strided(B, T, H, N, r, kbar, v, x, uprime, state_
                                        batch_stride, out_dtype, stream=None):
     _call("wkv6_finch_c2_prefill_bf16_strided", B, T, H, N, r, kbar, v, x, uprime, state_in, out,
           state_out, stream, ctypes.c_longlong(batch_stride), int(out_dtype))
+
+
+def wkv6_append_bf16(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):
+    _call("wkv6_append_bf16", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream)
+
+
+def wkv6_finch_c2_append_bf16(B, T, H, N, r, kbar, v, x, uprime, state_in, out, state_out, stream=None):
+    _call("wkv6_finch_c2_append_bf16", B, T, H, N, r, kbar, v, x, uprime, state_in, out, state_out, stream)
+
+
+def wkv6_decode_bf16(B, H, N, r, k, v, x, u, state, out, stream=None):
+    _check(load().wkv6_decode_bf16(B, H, N, _ptr(r), _ptr(k), _ptr(v), _ptr(x), _ptr(u), _ptr(state),
+                                   _ptr(out), _stream(stream)))
+
+
+def wkv6_finch_c2_decode_bf16(B, H, N, r, kbar, v, x, uprime, state, out, stream=None):
+    _check(load().wkv6_finch_c2_decode_bf16(B, H, N, _ptr(r), _ptr(kbar), _ptr(v), _ptr(x), _ptr(uprime),
+                                            _ptr(state), _ptr(out), _stream(stream)))
 
 
 def wkv6_version():

@@ -9,7 +9,13 @@ namespace {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<std::uintptr_t>(p) & 15u) != 0; }
 
-enum class Path { kChunked, kRecurrent };
+enum class Path { kChunked, kRecurrent, kBySize };
+
+// Sequences at most this long go to the token-by-token kernel when the caller leaves the
+// choice to the library (append / decode shapes): with thousands of (batch, head) units and
+// a few tokens each the work is streaming the state once, and the chunked kernel's pipeline
+// of five windows per workgroup never fills.  Measured crossover on MI355X: about 20 tokens.
+constexpr int kRecurrentMaxTokens = 16;
 
 // `uprime` selects the form: nullptr = Finch (bonus u), otherwise Finch-C2 (u unused, may be null).
 int run(int B, int T, int H, int N, const void* r, const void* k, const void* v, const void* x,
@@ -44,8 +50,8 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     hipError_t err;
     if (T == 0)
         err = wkv6::launch_state_passthrough(a, s);
-    else if (path == Path::kRecurrent)
-        err = wkv6::launch_recurrent(a, in_bf16, s);
+    else if (path == Path::kRecurrent || (path == Path::kBySize && T <= kRecurrentMaxTokens))
+        err = wkv6::launch_recurrent(a, in_bf16, in_bf16 && !out_f32, s);
     else
         err = wkv6::launch_chunked(a, out_f32 ? wkv6::ChunkedMode::kF32Out : wkv6::ChunkedMode::kBf16Out, s);
     return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
@@ -102,6 +108,35 @@ int wkv6_finch_c2_prefill_bf16_strided(int B, int T, int H, int N, const void* r
                out_dtype == WKV6_DTYPE_F32, Path::kChunked, stream, uprime, true);
 }
 
+int wkv6_append_bf16(int B, int T, int H, int N, const void* r, const void* k, const void* v,
+                     const void* x, const float* u, const float* state_in, void* out,
+                     float* state_out, void* stream) {
+    return run(B, T, H, N, r, k, v, x, u, state_in, out, state_out,
+               static_cast<long long>(T) * H * N, true, false, Path::kBySize, stream);
+}
+
+int wkv6_finch_c2_append_bf16(int B, int T, int H, int N, const void* r, const void* kbar,
+                              const void* v, const void* x, const void* uprime,
+                              const float* state_in, void* out, float* state_out, void* stream) {
+    return run(B, T, H, N, r, kbar, v, x, nullptr, state_in, out, state_out,
+               static_cast<long long>(T) * H * N, true, false, Path::kBySize, stream, uprime, true);
+}
+
+int wkv6_decode_bf16(int B, int H, int N, const void* r, const void* k, const void* v,
+                     const void* x, const float* u, float* state, void* out, void* stream) {
+    if (!state) return WKV6_ERR_NULL;
+    return run(B, 1, H, N, r, k, v, x, u, state, out, state,
+               static_cast<long long>(H) * N, true, false, Path::kRecurrent, stream);
+}
+
+int wkv6_finch_c2_decode_bf16(int B, int H, int N, const void* r, const void* kbar, const void* v,
+                              const void* x, const void* uprime, float* state, void* out,
+                              void* stream) {
+    if (!state) return WKV6_ERR_NULL;
+    return run(B, 1, H, N, r, kbar, v, x, nullptr, state, out, state,
+               static_cast<long long>(H) * N, true, false, Path::kRecurrent, stream, uprime, true);
+}
+
 int wkv6_prefill_f32(int B, int T, int H, int N, const float* r, const float* k, const float* v,
                      const float* x, const float* u, const float* state_in, float* out,
                      float* state_out, void* stream) {
@@ -129,7 +164,7 @@ const char* wkv6_status_string(int status) {
     }
 }
 
-int wkv6_version(void) { return 200; }
+int wkv6_version(void) { return 300; }
 
 }  // extern "C"
 

@@ -32,8 +32,9 @@ struct Args {
 
 enum class ChunkedMode { kBf16Out, kF32Out, kStateOnly };
 
-// Token-by-token fp32 kernel; inputs bf16 or fp32, out always fp32.
-hipError_t launch_recurrent(const Args& a, bool in_bf16, hipStream_t stream);
+// Token-by-token fp32 kernel; inputs bf16 or fp32 (fp32 inputs: fp32 out, Finch form only);
+// with bf16 inputs the output is fp32 or bf16 and a.uprime selects the Finch-C2 form.
+hipError_t launch_recurrent(const Args& a, bool in_bf16, bool out_bf16, hipStream_t stream);
 
 // Chunked matrix-core kernel; inputs bf16, out bf16 or fp32, or (kStateOnly) no output at all:
 // only state_out and decay_out of every unit, from r-independent work.

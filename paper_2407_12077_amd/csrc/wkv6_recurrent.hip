@@ -5,7 +5,11 @@
 //     o_t[j] = sum_i r_t[i] S[i][j]  +  (sum_i r_t[i] u[i] k_t[i]) v_t[j]
 //     S[i][j] = w_t[i] S[i][j] + k_t[i] v_t[j],   w_t = exp(-exp(x_t))
 // It is bound by the fp32 vector ALUs (about 3*N*N operations per token and head), which
-// is why the chunked kernel exists; this one serves fp32 tensors and cross-checks.
+// is why the chunked kernel exists; this one serves fp32 tensors, cross-checks, and the
+// decode / short-append shapes (one or a few tokens per sequence, many sequences), where the
+// work is streaming the fp32 state through once: 64 row loads of 256 contiguous bytes per
+// wave, all in flight together.
+// Finch-C2 form (template flag): k = kbar (1 - w), no bonus, second value u' added to o.
 #include "wkv6_launch.h"
 
 #include <hip/hip_bf16.h>
@@ -29,7 +33,7 @@ __device__ __forceinline__ float wave_sum(float a) {
     return a;
 }
 
-template <bool kInBf16>
+template <bool kInBf16, bool kOutBf16, bool kC2>
 __global__ __launch_bounds__(64) void recurrent_kernel(Args a) {
     constexpr int N = kHeadSize;
     const int unit = blockIdx.x;           // b * H + h
@@ -51,21 +55,22 @@ __global__ __launch_bounds__(64) void recurrent_kernel(Args a) {
         for (int i = 0; i < N; ++i) S[i] = 0.f;
     }
 
-    const float uj = a.u[h * N + j];
+    const float uj = kC2 ? 0.f : a.u[h * N + j];
     const long long tok_stride = static_cast<long long>(a.H) * N;
     long long idx = static_cast<long long>(b) * a.batch_stride + static_cast<long long>(h) * N + j;
-    float* out = static_cast<float*>(a.out);
 
-    float rj = 0.f, kj = 0.f, vj = 0.f, xj = 0.f;
+    float rj = 0.f, kj = 0.f, vj = 0.f, xj = 0.f, pj = 0.f;
     if (a.T > 0) {
         rj = load_in<kInBf16>(a.r, idx);
         kj = load_in<kInBf16>(a.k, idx);
         vj = load_in<kInBf16>(a.v, idx);
         xj = load_in<kInBf16>(a.x, idx);
+        if constexpr (kC2) pj = load_in<kInBf16>(a.uprime, idx);
     }
     for (int t = 0; t < a.T; ++t) {
-        const float r_cur = rj, k_cur = kj, v_cur = vj;
+        const float r_cur = rj, v_cur = vj, p_cur = pj;
         const float w_cur = expf(-expf(xj));
+        const float k_cur = kC2 ? kj * (1.f - w_cur) : kj;
         const long long idx_cur = idx;
         idx += tok_stride;
         if (t + 1 < a.T) {                     // next token's loads overlap this token's math
@@ -73,15 +78,16 @@ __global__ __launch_bounds__(64) void recurrent_kernel(Args a) {
             kj = load_in<kInBf16>(a.k, idx);
             vj = load_in<kInBf16>(a.v, idx);
             xj = load_in<kInBf16>(a.x, idx);
+            if constexpr (kC2) pj = load_in<kInBf16>(a.uprime, idx);
         }
         __syncthreads();                       // previous token's LDS reads are done
         s_r[j] = r_cur;
         s_k[j] = k_cur;
         s_w[j] = w_cur;
-        const float ruk = wave_sum(r_cur * uj * k_cur);
+        float o = p_cur;                       // Finch-C2: the second value; Finch: the bonus term
+        if constexpr (!kC2) o = wave_sum(r_cur * uj * k_cur) * v_cur;
         __syncthreads();
 
-        float o = ruk * v_cur;
 #pragma unroll
         for (int i4 = 0; i4 < N; i4 += 4) {
             const float4 r4 = *reinterpret_cast<const float4*>(&s_r[i4]);
@@ -96,7 +102,11 @@ __global__ __launch_bounds__(64) void recurrent_kernel(Args a) {
             o = fmaf(r4.w, S[i4 + 3], o);
             S[i4 + 3] = fmaf(w4.w, S[i4 + 3], k4.w * v_cur);
         }
-        out[idx_cur] = o;
+        if constexpr (kOutBf16)
+            static_cast<unsigned short*>(a.out)[idx_cur] =
+                __builtin_bit_cast(unsigned short, static_cast<__bf16>(o));
+        else
+            static_cast<float*>(a.out)[idx_cur] = o;
     }
 
     if (a.state_out) {
@@ -118,12 +128,19 @@ __global__ __launch_bounds__(256) void state_passthrough_kernel(const float* in,
 
 }  // namespace
 
-hipError_t launch_recurrent(const Args& a, bool in_bf16, hipStream_t stream) {
+hipError_t launch_recurrent(const Args& a, bool in_bf16, bool out_bf16, hipStream_t stream) {
     const dim3 grid(static_cast<unsigned>(a.B) * static_cast<unsigned>(a.H));
-    if (in_bf16)
-        hipLaunchKernelGGL(recurrent_kernel<true>, grid, dim3(64), 0, stream, a);
+    const bool c2 = a.uprime != nullptr;
+    if (!in_bf16)
+        hipLaunchKernelGGL((recurrent_kernel<false, false, false>), grid, dim3(64), 0, stream, a);
+    else if (!out_bf16 && !c2)
+        hipLaunchKernelGGL((recurrent_kernel<true, false, false>), grid, dim3(64), 0, stream, a);
+    else if (!out_bf16 && c2)
+        hipLaunchKernelGGL((recurrent_kernel<true, false, true>), grid, dim3(64), 0, stream, a);
+    else if (!c2)
+        hipLaunchKernelGGL((recurrent_kernel<true, true, false>), grid, dim3(64), 0, stream, a);
     else
-        hipLaunchKernelGGL(recurrent_kernel<false>, grid, dim3(64), 0, stream, a);
+        hipLaunchKernelGGL((recurrent_kernel<true, true, true>), grid, dim3(64), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -74,6 +74,21 @@ def test_finch_c2_validation_happens_before_any_launch(name):
     assert g(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64, 7, None) == 3
 
 
+def test_decode_and_append_validation():
+    f = _raw("wkv6_decode_bf16")
+    assert f(2, 3, 64, A, A, A, A, A, None, A, None) == 1                # state is required
+    assert f(2, 3, 32, A, A, A, A, A, A, A, None) == 3
+    assert f(2, 0, 64, A, A, A, A, A, A, A, None) == 2
+    assert f(2, 3, 64, A, A, A, A, None, A, A, None) == 1                # u
+    g = _raw("wkv6_finch_c2_decode_bf16")
+    assert g(2, 3, 64, A, A, A, A, None, A, A, None) == 1                # uprime
+    assert g(2, 3, 64, A, A, A, A, A, None, A, None) == 1
+    h = _raw("wkv6_append_bf16")
+    assert h(1, 8, 2, 32, A, A, A, A, A, None, A, A, None) == 3
+    assert h(1, 8, 2, 64, A, None, A, A, A, None, A, A, None) == 1
+    assert _raw("wkv6_finch_c2_append_bf16")(1, 8, 2, 64, A, A, A, A, None, None, A, A, None) == 1
+
+
 def test_strided_entry_validation():
     f = _raw("wkv6_prefill_bf16_strided")
     assert f(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64 - 8, 1, None) == 2   # stride < T*H*N
