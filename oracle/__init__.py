@@ -11,6 +11,9 @@ and never imports it.
 ``finch_c2_oracle`` / ``finch_c2_numpy``
                   the Finch-C2 form of the time mix (key times one minus the decay, second
                   value added to the read-out, no bonus), ``finch_c2_oracle.c`` and its twin.
+``key_compress_oracle``
+                  the GOLD key compression c_t = x_t W^KD as three plain loops
+                  (``key_compress_oracle.c``).
 """
-from .cbuild import build_oracle, finch_c2_oracle, wkv6_oracle  # noqa: F401
+from .cbuild import build_oracle, finch_c2_oracle, key_compress_oracle, wkv6_oracle  # noqa: F401
 from .wkv6_numpy import finch_c2_numpy, wkv6_numpy  # noqa: F401

@@ -8,6 +8,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "wkv6_oracle.c")
 _SRC_C2 = os.path.join(_HERE, "finch_c2_oracle.c")
+_SRC_KC = os.path.join(_HERE, "key_compress_oracle.c")
 _LIB = os.path.join(_HERE, "libwkv6_oracle.so")
 _handle = None
 
@@ -15,10 +16,10 @@ _handle = None
 def build_oracle(force=False):
     """Compile the oracle's C sources with the host C compiler (no fast-math)."""
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
-        os.path.getmtime(_SRC), os.path.getmtime(_SRC_C2))
+        os.path.getmtime(_SRC), os.path.getmtime(_SRC_C2), os.path.getmtime(_SRC_KC))
     if force or stale:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-pthread",
-               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC_C2, "-lm"]
+               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC_C2, _SRC_KC, "-lm"]
         subprocess.check_call(cmd)
     return _LIB
 
@@ -33,6 +34,9 @@ def _lib():
         lib.wkv6_oracle_f64.argtypes = [ctypes.c_int] * 4 + [fp] * 6 + [dp, dp, ctypes.c_int]
         lib.finch_c2_oracle_f64.restype = ctypes.c_int
         lib.finch_c2_oracle_f64.argtypes = [ctypes.c_int] * 4 + [fp] * 6 + [dp, dp, ctypes.c_int]
+        lib.key_compress_oracle_f64.restype = ctypes.c_int
+        lib.key_compress_oracle_f64.argtypes = [ctypes.c_longlong, ctypes.c_int, ctypes.c_int, fp, fp, dp,
+                                                ctypes.c_int]
         _handle = lib
     return _handle
 
@@ -107,3 +111,28 @@ def finch_c2_oracle(r, kbar, v, x, uprime, state_in=None, nthreads=None):
     if rc != 0:
         raise RuntimeError(f"finch_c2_oracle_f64 failed with status {rc}")
     return out, sout
+
+
+def key_compress_oracle(x, w, nthreads=None):
+    """c = x W in fp64 (GOLD Key Compression): x [M, D] (or [..., D]), w [D, C].  Returns [M, C]
+    (leading axes of x kept) float64."""
+    x = np.asarray(x)
+    w = np.asarray(w)
+    lead = x.shape[:-1]
+    D = x.shape[-1]
+    if w.ndim != 2 or w.shape[0] != D:
+        raise ValueError(f"w: expected shape ({D}, C), got {w.shape}")
+    C = w.shape[1]
+    x2 = np.ascontiguousarray(x.reshape(-1, D), dtype=np.float32)
+    w2 = np.ascontiguousarray(w, dtype=np.float32)
+    M = x2.shape[0]
+    c = np.empty((M, C), dtype=np.float64)
+    if nthreads is None:
+        nthreads = os.cpu_count() or 1
+    fp = ctypes.POINTER(ctypes.c_float)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = _lib().key_compress_oracle_f64(M, D, C, x2.ctypes.data_as(fp), w2.ctypes.data_as(fp),
+                                        c.ctypes.data_as(dp), int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"key_compress_oracle_f64 failed with status {rc}")
+    return c.reshape(*lead, C)
