@@ -63,6 +63,64 @@ def cpu_baseline(cfg, inp, finch_c2=False):
                       f"({nb * cfg.T * cfg.H} token-heads, fp64 sequential recurrence, {dt:.2f} s)"}
 
 
+def bench_key_compress(args, torch, wkv):
+    """The step after the path: c = x W^KD for the tokens of the chosen configuration (B*T tokens,
+    D = H*N), x and W^KD resident in HBM, bf16 output."""
+    from oracle import key_compress_oracle
+    from paper_2407_12077_amd.workloads import CONFIGS, make_key_compress_inputs
+    cfg = CONFIGS[args.config]
+    M, D = cfg.B * cfg.T, cfg.H * cfg.N
+    C = D // 16
+    x, w = make_key_compress_inputs(M, D)
+    xd = torch.from_numpy(x).to(torch.bfloat16).cuda()
+    wd = torch.from_numpy(w).to(torch.bfloat16).cuda()
+    c = torch.empty((M, C), dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        wkv.wkv6_key_compress_bf16(M, D, xd, wd, c, wkv.WKV6_DTYPE_BF16, stream.cuda_stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record(stream)
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
+    ms_per_step = wall * 1e3 / args.steps
+    abytes = M * D * 2 + D * C * 2 + M * C * 2
+    aflops = 2 * M * D * C
+    achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    result = {
+        "metric": "GOLD key compression tokens/s (D=%d, D/16=%d, bf16)" % (D, C),
+        "value": M / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 operands, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"key compression of config {cfg.index}'s tokens: M={M} D={D}",
+                   "entry": args.entry, "global_batch": cfg.B, "seq_len": cfg.T},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel_ms_avg": kernel_ms,
+                     "kernel_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
+                     "kernel_ms_min": min(per_launch_ms), "algorithmic_bytes": abytes,
+                     "mfma_frac": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
+    }
+    if not args.no_cpu_baseline:
+        cores = min(os.cpu_count() or 1, 16)
+        nrows = min(M, 4096)
+        t0 = time.perf_counter()
+        key_compress_oracle(x[:nrows], w, nthreads=cores)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": nrows / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                                  "sample": f"first {nrows} of {M} tokens, fp64 triple loop, {dt:.2f} s"}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,7 +130,8 @@ def main():
     ap.add_argument("--entry", default="wkv6_prefill_bf16",
                     choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent",
                              "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
-                             "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_decode_bf16"])
+                             "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_decode_bf16",
+                             "wkv6_key_compress_bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 512 MiB device copy (calibrates rocprofv3 byte counters)")
@@ -88,6 +147,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     wkv.load()                                   # fails loudly if the HIP library is missing
+    if args.entry == "wkv6_key_compress_bf16":
+        return bench_key_compress(args, torch, wkv)
     cfg = CONFIGS[args.config]
     decode = args.entry == "wkv6_decode_bf16"
     if decode:

@@ -183,6 +183,21 @@ int wkv6_finch_c2_append_bf16(int B, int T, int H, int N,
                               const void *uprime, const float *state_in,
                               void *out, float *state_out, void *stream);
 
+/*
+ * GOLD key compression (paper: Method, "GOLD Key Compression"): the step that turns the output
+ * of the last Finch-C2 layer into the compressed key cache,  c_t = x_t W^KD,  W^KD with D rows
+ * and D/16 columns.  A skinny matrix product bound by the one HBM read of x; bf16 operands,
+ * fp32 accumulation on the matrix cores, one rounding of the result.
+ *   M      tokens (batch x sequence, any M >= 0; 0 is a no-op)
+ *   D      model dimension, a multiple of 2048 (other values: WKV6_ERR_UNSUPPORTED)
+ *   x      [M][D]     bf16 device pointer, 16-byte aligned
+ *   w_kd   [D][D/16]  bf16, row-major as the paper writes it (x on the left)
+ *   c      [M][D/16]  bf16 or fp32 per out_dtype (a wkv6_dtype)
+ * Enqueues one kernel on `stream`; allocates nothing; errors as for the other entry points.
+ */
+int wkv6_key_compress_bf16(long long M, int D, const void *x, const void *w_kd, void *c,
+                           int out_dtype, void *stream);
+
 /* All-fp32 tensors.  Token-by-token kernel with the state in fp32 registers. */
 int wkv6_prefill_f32(int B, int T, int H, int N,
                      const float *r, const float *k, const float *v, const float *x,

@@ -20,7 +20,7 @@ EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_s
            "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_finch_c2_prefill_bf16",
            "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_strided",
            "wkv6_decode_bf16", "wkv6_finch_c2_decode_bf16", "wkv6_append_bf16",
-           "wkv6_finch_c2_append_bf16", "wkv6_status_string", "wkv6_version")
+           "wkv6_finch_c2_append_bf16", "wkv6_key_compress_bf16", "wkv6_status_string", "wkv6_version")
 
 _lib = None
 
@@ -56,6 +56,8 @@ def load():
             fn = getattr(lib, name)
             fn.restype = i
             fn.argtypes = [i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.wkv6_key_compress_bf16.restype = i
+        lib.wkv6_key_compress_bf16.argtypes = [ll, i, vp, vp, vp, i, vp]
         lib.wkv6_prefill_bf16_split.restype = i
         lib.wkv6_prefill_bf16_split.argtypes = common + [i, i, vp, ll, vp]
         lib.wkv6_split_workspace_bytes.restype = ll
@@ -164,6 +166,10 @@ def wkv6_decode_bf16(B, H, N, r, k, v, x, u, state, out, stream=None):
 def wkv6_finch_c2_decode_bf16(B, H, N, r, kbar, v, x, uprime, state, out, stream=None):
     _check(load().wkv6_finch_c2_decode_bf16(B, H, N, _ptr(r), _ptr(kbar), _ptr(v), _ptr(x), _ptr(uprime),
                                             _ptr(state), _ptr(out), _stream(stream)))
+
+
+def wkv6_key_compress_bf16(M, D, x, w_kd, c, out_dtype, stream=None):
+    _check(load().wkv6_key_compress_bf16(M, D, _ptr(x), _ptr(w_kd), _ptr(c), int(out_dtype), _stream(stream)))
 
 
 def wkv6_version():

@@ -152,6 +152,19 @@ int wkv6_prefill_bf16_recurrent(int B, int T, int H, int N, const void* r, const
                static_cast<long long>(T) * H * N, true, true, Path::kRecurrent, stream);
 }
 
+int wkv6_key_compress_bf16(long long M, int D, const void* x, const void* w_kd, void* c, int out_dtype,
+                           void* stream) {
+    if (out_dtype != WKV6_DTYPE_BF16 && out_dtype != WKV6_DTYPE_F32) return WKV6_ERR_UNSUPPORTED;
+    if (D < 2048 || D % 2048 != 0 || D > 65536) return WKV6_ERR_UNSUPPORTED;
+    if (M < 0 || M > 0x7fffffffLL * 128) return WKV6_ERR_SHAPE;
+    if (M == 0) return WKV6_OK;
+    if (!x || !w_kd || !c) return WKV6_ERR_NULL;
+    if (misaligned(x) || misaligned(w_kd) || misaligned(c)) return WKV6_ERR_ALIGN;
+    const hipError_t err = wkv6::launch_key_compress(M, D, x, w_kd, c, out_dtype == WKV6_DTYPE_F32,
+                                                     static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
+}
+
 const char* wkv6_status_string(int status) {
     switch (status) {
         case WKV6_OK: return "ok";
@@ -164,7 +177,7 @@ const char* wkv6_status_string(int status) {
     }
 }
 
-int wkv6_version(void) { return 300; }
+int wkv6_version(void) { return 400; }
 
 }  // extern "C"
 

@@ -46,6 +46,11 @@ hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream);
 hipError_t launch_combine_segments(int B, int H, int segs, const float* state_in, float* seg_state,
                                    const float* seg_decay, float* state_out, hipStream_t stream);
 
+// GOLD key compression c = x W: x [M][D] bf16, w [D][D/16] bf16, c [M][D/16] bf16 or fp32.
+// D must be a multiple of 2048 (128 output columns per workgroup).
+hipError_t launch_key_compress(long long M, int D, const void* x, const void* w, void* c, bool out_f32,
+                               hipStream_t stream);
+
 // T == 0: state_out = state_in (or zero).
 hipError_t launch_state_passthrough(const Args& a, hipStream_t stream);
 

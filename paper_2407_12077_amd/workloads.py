@@ -130,3 +130,15 @@ def make_uprime(cfg, seed=None):
     a = rng.standard_normal((cfg.B, cfg.T, cfg.H, cfg.N), dtype=np.float32)
     a *= np.float32(1.0 / np.sqrt(cfg.N))
     return round_to_bf16(a) if cfg.dtype == "bf16" else a
+
+
+def make_key_compress_inputs(M, D, seed=BASE_SEED + 100):
+    """Inputs of the GOLD key compression for M tokens of a model of width D: hidden states
+    x [M, D] ~ N(0, 1) (a residual-stream activation stands in for the last Finch-C2 layer's
+    output) and the compression matrix w_kd [D, D/16] ~ N(0, 1/D) (so the compressed entries have
+    unit scale), both rounded to bf16 and returned as float32 arrays."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = rng.standard_normal((M, D), dtype=np.float32)
+    w = rng.standard_normal((D, D // 16), dtype=np.float32)
+    w *= np.float32(1.0 / np.sqrt(D))
+    return round_to_bf16(x), round_to_bf16(w)

@@ -89,6 +89,16 @@ def test_decode_and_append_validation():
     assert _raw("wkv6_finch_c2_append_bf16")(1, 8, 2, 64, A, A, A, A, None, None, A, A, None) == 1
 
 
+def test_key_compress_validation():
+    f = _raw("wkv6_key_compress_bf16")
+    assert f(4, 1024, A, A, A, 0, None) == 3               # D not a multiple of 2048
+    assert f(4, 2048, A, A, A, 5, None) == 3               # dtype code
+    assert f(-4, 2048, A, A, A, 0, None) == 2
+    assert f(4, 2048, A, None, A, 0, None) == 1
+    assert f(4, 2048, P(0x1008), A, A, 0, None) == 5
+    assert f(0, 2048, None, None, None, 0, None) == 0
+
+
 def test_strided_entry_validation():
     f = _raw("wkv6_prefill_bf16_strided")
     assert f(2, 8, 2, 64, A, A, A, A, A, None, A, A, 8 * 2 * 64 - 8, 1, None) == 2   # stride < T*H*N
