@@ -153,6 +153,14 @@ int wkv6_finch_c2_prefill_bf16_strided(int B, int T, int H, int N,
                                        void *out, float *state_out,
                                        long long batch_stride, int out_dtype, void *stream);
 
+/* Token-split variant of the Finch-C2 form: wkv6_prefill_bf16_split with kbar and uprime in
+ * place of k and u; same passes, same workspace size. */
+int wkv6_finch_c2_prefill_bf16_split(int B, int T, int H, int N,
+                                     const void *r, const void *kbar, const void *v, const void *x,
+                                     const void *uprime, const float *state_in,
+                                     void *out, float *state_out, int out_dtype, int segments,
+                                     void *workspace, long long workspace_bytes, void *stream);
+
 /*
  * Serving shapes: the same recurrence for one token (decode) or a few tokens (append) per
  * sequence and many sequences, where the cost is streaming each fp32 state through once

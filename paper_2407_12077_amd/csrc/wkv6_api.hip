@@ -41,6 +41,7 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     wkv6::Args a;
     a.B = B; a.T = T; a.H = H;
     a.r = r; a.k = k; a.v = v; a.x = x; a.u = u;
+    a.finch_c2 = finch_c2;
     a.uprime = finch_c2 ? uprime : nullptr;
     a.state_in = state_in; a.out = out; a.state_out = state_out;
     a.batch_stride = batch_stride;
@@ -225,10 +226,14 @@ long long wkv6_split_workspace_bytes(int B, int T, int H, int N, int segments) {
     return static_cast<long long>(B) * p.segs * H * (wkv6::kHeadSize * wkv6::kHeadSize + wkv6::kHeadSize) * 4;
 }
 
-int wkv6_prefill_bf16_split(int B, int T, int H, int N, const void* r, const void* k, const void* v,
-                            const void* x, const float* u, const float* state_in, void* out,
-                            float* state_out, int out_dtype, int segments, void* workspace,
-                            long long workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+int run_split(int B, int T, int H, int N, const void* r, const void* k, const void* v, const void* x,
+              const float* u, const void* uprime, bool finch_c2, const float* state_in, void* out,
+              float* state_out, int out_dtype, int segments, void* workspace,
+              long long workspace_bytes, void* stream) {
     if (out_dtype != WKV6_DTYPE_BF16 && out_dtype != WKV6_DTYPE_F32) return WKV6_ERR_UNSUPPORTED;
     if (N != wkv6::kHeadSize) return WKV6_ERR_UNSUPPORTED;
     if (B < 0 || T < 0 || H < 1 || H > 262144 || segments < 1) return WKV6_ERR_SHAPE;
@@ -236,10 +241,12 @@ int wkv6_prefill_bf16_split(int B, int T, int H, int N, const void* r, const voi
     if (T == 0 || B == 0 || p.segs == 1)
         return run(B, T, H, N, r, k, v, x, u, state_in, out, state_out,
                    static_cast<long long>(T) * H * N, true, out_dtype == WKV6_DTYPE_F32,
-                   Path::kChunked, stream);
-    if (!u || !r || !k || !v || !x || !out || !workspace) return WKV6_ERR_NULL;
+                   Path::kChunked, stream, uprime, finch_c2);
+    if ((!finch_c2 && !u) || (finch_c2 && !uprime) || !r || !k || !v || !x || !out || !workspace)
+        return WKV6_ERR_NULL;
     if (misaligned(r) || misaligned(k) || misaligned(v) || misaligned(x) || misaligned(out) ||
-        misaligned(u) || misaligned(state_in) || misaligned(state_out) || misaligned(workspace))
+        misaligned(u) || misaligned(uprime) || misaligned(state_in) || misaligned(state_out) ||
+        misaligned(workspace))
         return WKV6_ERR_ALIGN;
     if (workspace_bytes < wkv6_split_workspace_bytes(B, T, H, N, segments)) return WKV6_ERR_SHAPE;
     if (static_cast<long long>(B) * p.segs * H > 0x7fffffffLL) return WKV6_ERR_SHAPE;
@@ -251,7 +258,8 @@ int wkv6_prefill_bf16_split(int B, int T, int H, int N, const void* r, const voi
     wkv6::Args a;
     a.B = B; a.T = p.seg_len; a.H = H;
     a.r = r; a.k = k; a.v = v; a.x = x; a.u = u;
-    a.uprime = nullptr;
+    a.finch_c2 = finch_c2;
+    a.uprime = finch_c2 ? uprime : nullptr;
     a.batch_stride = static_cast<long long>(T) * H * N;
     a.segs = p.segs; a.T_last = p.last_len;
     a.seg_stride = static_cast<long long>(p.seg_len) * H * N;
@@ -267,6 +275,27 @@ int wkv6_prefill_bf16_split(int B, int T, int H, int N, const void* r, const voi
                                                                : wkv6::ChunkedMode::kBf16Out;
     if (wkv6::launch_chunked(a, mode, s) != hipSuccess) return WKV6_ERR_LAUNCH;
     return WKV6_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wkv6_prefill_bf16_split(int B, int T, int H, int N, const void* r, const void* k, const void* v,
+                            const void* x, const float* u, const float* state_in, void* out,
+                            float* state_out, int out_dtype, int segments, void* workspace,
+                            long long workspace_bytes, void* stream) {
+    return run_split(B, T, H, N, r, k, v, x, u, nullptr, false, state_in, out, state_out, out_dtype,
+                     segments, workspace, workspace_bytes, stream);
+}
+
+int wkv6_finch_c2_prefill_bf16_split(int B, int T, int H, int N, const void* r, const void* kbar,
+                                     const void* v, const void* x, const void* uprime,
+                                     const float* state_in, void* out, float* state_out,
+                                     int out_dtype, int segments, void* workspace,
+                                     long long workspace_bytes, void* stream) {
+    return run_split(B, T, H, N, r, kbar, v, x, nullptr, uprime, true, state_in, out, state_out,
+                     out_dtype, segments, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

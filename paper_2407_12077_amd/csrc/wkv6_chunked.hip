@@ -702,11 +702,11 @@ hipError_t launch_mode(const Args& a, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream) {
-    const bool c2 = a.uprime != nullptr;             // Finch-C2 form: second value instead of bonus
+    const bool c2 = a.finch_c2;
     switch (mode) {
         case ChunkedMode::kBf16Out: return c2 ? launch_mode<0, true>(a, stream) : launch_mode<0, false>(a, stream);
         case ChunkedMode::kF32Out: return c2 ? launch_mode<1, true>(a, stream) : launch_mode<1, false>(a, stream);
-        default: return launch_mode<2, false>(a, stream);
+        default: return c2 ? launch_mode<2, true>(a, stream) : launch_mode<2, false>(a, stream);
     }
 }
 

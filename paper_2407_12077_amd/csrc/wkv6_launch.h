@@ -12,10 +12,11 @@ struct Args {
     const void* k;
     const void* v;
     const void* x;
-    const float* u;           // Finch bonus [H][N]; unused when uprime is set
-    const void* uprime;       // nullptr: Finch form.  Otherwise the Finch-C2 form: k is the key before its
-                              // (1 - w) factor, no bonus, and this second value [B][T][H][N] (bf16, laid out
-                              // like out) is added to the read-out
+    const float* u;           // Finch bonus [H][N]; unused in the Finch-C2 form
+    bool finch_c2;            // false: Finch form (bonus u).  true: Finch-C2 form: k is the key before its
+                              // (1 - w) factor, no bonus, and the second value uprime is added to the read-out
+    const void* uprime;       // Finch-C2 only: [B][T][H][N] bf16, laid out like out; not read by the
+                              // state-only pass
     const float* state_in;    // may be nullptr (zero state)
     void* out;
     float* state_out;         // may be nullptr (not written)
@@ -33,7 +34,7 @@ struct Args {
 enum class ChunkedMode { kBf16Out, kF32Out, kStateOnly };
 
 // Token-by-token fp32 kernel; inputs bf16 or fp32 (fp32 inputs: fp32 out, Finch form only);
-// with bf16 inputs the output is fp32 or bf16 and a.uprime selects the Finch-C2 form.
+// with bf16 inputs the output is fp32 or bf16 and a.finch_c2 selects the form.
 hipError_t launch_recurrent(const Args& a, bool in_bf16, bool out_bf16, hipStream_t stream);
 
 // Chunked matrix-core kernel; inputs bf16, out bf16 or fp32, or (kStateOnly) no output at all:

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void state_passthrough_kernel(const float* in,
 
 hipError_t launch_recurrent(const Args& a, bool in_bf16, bool out_bf16, hipStream_t stream) {
     const dim3 grid(static_cast<unsigned>(a.B) * static_cast<unsigned>(a.H));
-    const bool c2 = a.uprime != nullptr;
+    const bool c2 = a.finch_c2;
     if (!in_bf16)
         hipLaunchKernelGGL((recurrent_kernel<false, false, false>), grid, dim3(64), 0, stream, a);
     else if (!out_bf16 && !c2)

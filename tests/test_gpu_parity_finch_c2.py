@@ -122,6 +122,25 @@ def test_state_passing_with_the_strided_entry(gpu_device):
             assert max_norm_err(o, o_full) <= 1e-6 and max_norm_err(s, s_full) <= 1e-6
 
 
+@pytest.mark.parametrize("T,segments", [(4096, 4), (1000, 7), (333, 3), (40, 8)])
+def test_split_matches_oracle(gpu_device, T, segments):
+    inp = inputs(scaled(CONFIGS[4], B=2, T=T, H=2))
+    B, T, H, N = inp["r"].shape
+    o_ref, s_ref = oracle(inp)
+    r, k, v, x, up = (to_dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "x", "uprime"))
+    s_in = to_dev(inp["state_in"], torch.float32)
+    out = torch.full((B, T, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    s_out = torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda")
+    nbytes = wkv.wkv6_split_workspace_bytes(B, T, H, N, segments)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    wkv.wkv6_finch_c2_prefill_bf16_split(B, T, H, N, r, k, v, x, up, s_in, out, s_out, wkv.WKV6_DTYPE_F32,
+                                         segments, ws, nbytes)
+    torch.cuda.synchronize()
+    eo = max_norm_err(out.cpu().numpy(), o_ref)
+    es = max_norm_err(s_out.cpu().numpy(), s_ref)
+    assert eo <= TOL_BF16 and es <= TOL_BF16, (eo, es)
+
+
 def test_validation(gpu_device):
     z = torch.zeros((1, 8, 2, 64), dtype=torch.bfloat16, device="cuda")
     out = torch.empty_like(z)
