@@ -24,8 +24,11 @@ MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 MFMA
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each
 # scaled by the same counter's reading for a plain copy kernel); see profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 262 262 KiB x 2.0 (copy calibration) + WRITE_SIZE 135 168 KiB x 1.0
-    "config2:wkv6_prefill_bf16": int(262262 * 1024 * 2.0 + 135168 * 1024 * 1.0),
+    # FETCH_SIZE (KiB) x 2.0 (copy calibration) + WRITE_SIZE (KiB) x 1.0
+    "config2:wkv6_prefill_bf16": int(262276 * 1024 * 2.0 + 135168 * 1024 * 1.0),
+    "config2:wkv6_finch_c2_prefill_bf16": int(327823 * 1024 * 2.0 + 135168 * 1024 * 1.0),
+    "config2:wkv6_decode_bf16": int(270381 * 1024 * 2.0 + 528384 * 1024 * 1.0),
+    "config2:wkv6_key_compress_bf16": int(67636 * 1024 * 2.0 + 8192 * 1024 * 1.0),
 }
 
 
@@ -105,7 +108,9 @@ def bench_key_compress(args, torch, wkv):
         "config": {"workload": f"key compression of config {cfg.index}'s tokens: M={M} D={D}",
                    "entry": args.entry, "global_batch": cfg.B, "seq_len": cfg.T},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel_ms_avg": kernel_ms,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"config{args.config}:{args.entry}"),
+                     "kernel_ms_avg": kernel_ms,
                      "kernel_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
                      "kernel_ms_min": min(per_launch_ms), "algorithmic_bytes": abytes,
                      "mfma_frac": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
