@@ -318,6 +318,27 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 #pragma unroll
         for (int g = 0; g < 8; ++g)
             own[g] = *reinterpret_cast<const float2*>(lds + kG + (g * 64 + 2 * cp) * 4);
+        // Writes are grouped by tile, the four tokens of a tile back to back, so that neighbouring
+        // writes pair up into two-address LDS instructions.  The tiles that need no multiplier go
+        // out first, right behind the reads of the group totals: at the start of a window every
+        // wave of the workgroup queues LDS work, and the totals take hundreds of cycles to return.
+        const int nat0 = 4 * g8 * kRow + 4 * cp;             // token 0 of the group, natural channel order
+        auto put4 = [&](int tile, unsigned v0, unsigned v1, unsigned v2, unsigned v3) {
+            lds_write_u32(lds, tile + nat0, v0);
+            lds_write_u32(lds, tile + nat0 + kRow, v1);
+            lds_write_u32(lds, tile + nat0 + 2 * kRow, v2);
+            lds_write_u32(lds, tile + nat0 + 3 * kRow, v3);
+        };
+        put4(kVT, pr.vt[0], pr.vt[1], pr.vt[2], pr.vt[3]);
+        if constexpr (!kStateOnly) {
+            // level 4: the even group of an 8-block holds keys, the odd one queries
+            put4(kZ4, q4 ? pr.rp[0] : pr.ks[0], q4 ? pr.rp[1] : pr.ks[1], q4 ? pr.rp[2] : pr.ks[2],
+                 q4 ? pr.rp[3] : pr.ks[3]);
+            put4(kZ2, pr.z2[0], pr.z2[1], pr.z2[2], pr.z2[3]);
+            put4(kQ1, pr.q1[0], pr.q1[1], pr.q1[2], pr.q1[3]);
+            put4(kK1, pr.k1[0], pr.k1[1], pr.k1[2], pr.k1[3]);
+        }
+        __builtin_amdgcn_sched_barrier(0);       // keep these writes ahead of the wait for the totals
 #pragma unroll
         for (int ch = 0; ch < 2; ++ch) {
             float o[8];
@@ -346,25 +367,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         const unsigned h_kt = pack_h2(m_kt[0], m_kt[1]);
         const unsigned h16 = pack_h2(m16[0], m16[1]);
         const unsigned h8 = pack_h2(m8[0], m8[1]);
-        // Writes are grouped by tile, the four tokens of a tile back to back and the one tile with
-        // its own column order last, so that neighbouring writes pair up into two-address LDS
-        // instructions.
-        const int nat0 = 4 * g8 * kRow + 4 * cp;             // token 0 of the group, natural channel order
-        auto put4 = [&](int tile, unsigned v0, unsigned v1, unsigned v2, unsigned v3) {
-            lds_write_u32(lds, tile + nat0, v0);
-            lds_write_u32(lds, tile + nat0 + kRow, v1);
-            lds_write_u32(lds, tile + nat0 + 2 * kRow, v2);
-            lds_write_u32(lds, tile + nat0 + 3 * kRow, v3);
-        };
-        put4(kVT, pr.vt[0], pr.vt[1], pr.vt[2], pr.vt[3]);
         put4(kKT, mul_h2(pr.ks[0], h_kt), mul_h2(pr.ks[1], h_kt), mul_h2(pr.ks[2], h_kt), mul_h2(pr.ks[3], h_kt));
         if constexpr (!kStateOnly) {
-            // level 4: the even group of an 8-block holds keys, the odd one queries
-            put4(kZ4, q4 ? pr.rp[0] : pr.ks[0], q4 ? pr.rp[1] : pr.ks[1], q4 ? pr.rp[2] : pr.ks[2],
-                 q4 ? pr.rp[3] : pr.ks[3]);
-            put4(kZ2, pr.z2[0], pr.z2[1], pr.z2[2], pr.z2[3]);
-            put4(kQ1, pr.q1[0], pr.q1[1], pr.q1[2], pr.q1[3]);
-            put4(kK1, pr.k1[0], pr.k1[1], pr.k1[2], pr.k1[3]);
             const unsigned* z16 = kQ16 ? pr.rp : pr.ks;
             const unsigned* z8 = kQ8 ? pr.rp : pr.ks;
             put4(kZ16, mul_h2(z16[0], h16), mul_h2(z16[1], h16), mul_h2(z16[2], h16), mul_h2(z16[3], h16));
