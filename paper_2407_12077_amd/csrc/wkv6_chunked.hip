@@ -164,18 +164,30 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const char* base, l
                                              static_cast<int>(left), 0x00020000);
 }
 
+// A chunk's loads are issued in two halves (x and r; k and v) so that two different phases can
+// share the cost of issuing them.
 template <bool kSkipR>
-__device__ __forceinline__ void load_rows(Raw& d, const Streams& st, int t0, const int (&voff)[4]) {
+__device__ __forceinline__ void load_rows_xr(Raw& d, const Streams& st, int t0, const int (&voff)[4]) {
     const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
-    const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r, off, st.span_bytes);
-    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(st.k, off, st.span_bytes);
-    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(st.v, off, st.span_bytes);
     const __amdgpu_buffer_rsrc_t rx = chunk_rsrc(st.x, off, st.span_bytes);
 #pragma unroll
+    for (int s = 0; s < 4; ++s) d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, 0);
+    if constexpr (!kSkipR) {
+        const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r, off, st.span_bytes);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, 0);
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) d.r[s] = 0u;
+    }
+}
+
+__device__ __forceinline__ void load_rows_kv(Raw& d, const Streams& st, int t0, const int (&voff)[4]) {
+    const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
+    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(st.k, off, st.span_bytes);
+    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(st.v, off, st.span_bytes);
+#pragma unroll
     for (int s = 0; s < 4; ++s) {
-        d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, 0);
-        if constexpr (!kSkipR) d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, 0);
-        else d.r[s] = 0u;
         d.k[s] = __builtin_amdgcn_raw_buffer_load_b32(rk, voff[s], 0, 0);
         d.v[s] = __builtin_amdgcn_raw_buffer_load_b32(rv, voff[s], 0, 0);
     }
@@ -478,9 +490,10 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 
     // A group spends three consecutive windows on each of its chunks c = pg, pg+3, ...:
     //   window c    phase D: decays and group products of chunk c from one of two raw register
-    //               sets, then the HBM loads of the group's chunk after next (c+6) into the same
-    //               set; they stay in flight for six windows.  Issued unconditionally: past the
-    //               end the descriptor is empty and the loads return zeros without touching memory.
+    //               sets, then the HBM loads of x and r of the group's chunk after next (c+6) into
+    //               the same set (k and v follow in phase S); they stay in flight for four to six
+    //               windows.  Issued unconditionally: past the end the descriptor is empty and the
+    //               loads return zeros without touching memory.
     //   window c+1  phase T: multipliers from all groups' decay totals, every operand tile.
     //   window c+2  phase S: score MFMAs, and the finished output rows of chunk c-2.
     // The three groups are one window apart, so every window sees one group in each phase
@@ -491,7 +504,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     auto cycle = [&](int c, Raw& buf) {
         if (c < nchunks) digest(c, buf);
         load_uprime(c - 2);                       // older than the chunk loads: waited for first
-        load_rows<kStateOnly>(buf, st, (c + 6) * kChunk, voff);
+        load_rows_xr<kStateOnly>(buf, st, (c + 6) * kChunk, voff);
         __syncthreads();                                                        // window barrier
         if (c < nchunks) write_tiles(c);
         __syncthreads();                                                        // window barrier
@@ -499,10 +512,13 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             if (c < nchunks) scores(c);
             if (c >= 2 && c - 2 < nchunks) store_rows(c - 2);
         }
+        load_rows_kv(buf, st, (c + 6) * kChunk, voff);    // the other half, from the phase with slack
         __syncthreads();                                                        // window barrier
     };
-    load_rows<kStateOnly>(raw_a, st, pg * kChunk, voff);
-    load_rows<kStateOnly>(raw_b, st, (pg + 3) * kChunk, voff);
+    load_rows_xr<kStateOnly>(raw_a, st, pg * kChunk, voff);
+    load_rows_kv(raw_a, st, pg * kChunk, voff);
+    load_rows_xr<kStateOnly>(raw_b, st, (pg + 3) * kChunk, voff);
+    load_rows_kv(raw_b, st, (pg + 3) * kChunk, voff);
     __syncthreads();                                                            // start barrier
     int done = 0;                                                               // windows passed
     for (; done < pg; ++done) {
