@@ -105,10 +105,13 @@ __device__ __forceinline__ unsigned short bf16_bits(float a) {
     return __builtin_bit_cast(unsigned short, static_cast<__bf16>(a));
 }
 
-// w = exp(-exp(x)) through two base-2 exponentials (x=-inf -> 1, x=+inf -> 0).
+// w = exp(-exp(x)) through two base-2 exponentials (x=-inf -> 1, x=+inf -> 0):
+// log2(e) * exp(x) = exp2(x * log2(e) + log2(log2(e))), so the factor of the second exponential
+// rides in the argument of the first.
 __device__ __forceinline__ float decay_of(float x) {
-    const float e = __builtin_amdgcn_exp2f(x * kLog2e);
-    return __builtin_amdgcn_exp2f(-kLog2e * e);
+    constexpr float kLog2Log2e = 0.5287663729448977f;
+    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, kLog2Log2e));
+    return __builtin_amdgcn_exp2f(-e);
 }
 
 __device__ __forceinline__ half8 lds_read_h8(const char* lds, int byte_off) {
