@@ -1,0 +1,87 @@
+"""The entry points only enqueue kernels on the caller's stream (no allocation, no memset, no
+synchronisation), so a serving loop can capture them in a HIP graph.  Each graph is replayed
+several times, with eager work and synchronisations in between, and every replay is compared
+with the eager result."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_12077_amd as wkv
+from paper_2407_12077_amd.workloads import CONFIGS, make_inputs, scaled
+
+from gpu_util import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_decode_steps_in_a_graph(gpu_device):
+    cfg = scaled(CONFIGS[4], B=8, T=4, H=4)
+    inp = make_inputs(cfg)
+    B, T, H, N = inp["r"].shape
+    r, k, v, x = (to_dev(inp[n], torch.bfloat16) for n in "rkvx")
+    u = to_dev(inp["u"], torch.float32)
+    s0 = to_dev(inp["state_in"], torch.float32)
+    steps = [[a[:, t].contiguous() for a in (r, k, v, x)] for t in range(T)]
+
+    def run(state, outs):
+        for t in range(T):
+            wkv.wkv6_decode_bf16(B, H, N, *steps[t], u, state, outs[t])
+
+    state_e = s0.clone()
+    outs_e = [torch.empty((B, H, N), dtype=torch.bfloat16, device="cuda") for _ in range(T)]
+    run(state_e, outs_e)
+    torch.cuda.synchronize()
+
+    state_g = s0.clone()
+    outs_g = [torch.empty((B, H, N), dtype=torch.bfloat16, device="cuda") for _ in range(T)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(state_g, outs_g)                      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(state_g, outs_g)
+    for replay in range(3):
+        state_g.copy_(s0)                         # eager work between the replays
+        for o in outs_g:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(state_g, state_e), replay
+        for a, b in zip(outs_g, outs_e):
+            assert torch.equal(a, b), replay
+
+
+def test_prefill_in_a_graph(gpu_device):
+    cfg = scaled(CONFIGS[4], B=2, T=300, H=3)
+    inp = make_inputs(cfg)
+    B, T, H, N = inp["r"].shape
+    r, k, v, x = (to_dev(inp[n], torch.bfloat16) for n in "rkvx")
+    u = to_dev(inp["u"], torch.float32)
+    s_in = to_dev(inp["state_in"], torch.float32)
+    out_e = torch.empty((B, T, H, N), dtype=torch.bfloat16, device="cuda")
+    s_e = torch.empty_like(s_in)
+    wkv.wkv6_prefill_bf16(B, T, H, N, r, k, v, x, u, s_in, out_e, s_e)
+    torch.cuda.synchronize()
+
+    out_g = torch.empty_like(out_e)
+    s_g = torch.empty_like(s_in)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        wkv.wkv6_prefill_bf16(B, T, H, N, r, k, v, x, u, s_in, out_g, s_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        wkv.wkv6_prefill_bf16(B, T, H, N, r, k, v, x, u, s_in, out_g, s_g)
+    for replay in range(3):
+        out_g.fill_(float("nan"))
+        s_g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e) and torch.equal(s_g, s_e), replay
