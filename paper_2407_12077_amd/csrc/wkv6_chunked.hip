@@ -140,6 +140,13 @@ __device__ __forceinline__ float4v mfma(half8 a, half8 b, float4v c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
+// Cache policy of the streams that are touched exactly once (r, k, v, x, u', out): the
+// non-temporal bit, so they do not displace each other in the caches on their way through.
+constexpr int kStreamOnce = 2;
+__device__ __forceinline__ void store_once(void* p, uint4v q) {
+    __builtin_nontemporal_store(q, static_cast<uint4v*>(p));
+}
+
 struct Raw {           // one chunk's inputs of a producer thread: 4 tokens x one channel pair
     unsigned r[4], k[4], v[4], x[4];
 };
@@ -174,11 +181,11 @@ __device__ __forceinline__ void load_rows_xr(Raw& d, const Streams& st, int t0, 
     const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
     const __amdgpu_buffer_rsrc_t rx = chunk_rsrc(st.x, off, st.span_bytes);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, 0);
+    for (int s = 0; s < 4; ++s) d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, kStreamOnce);
     if constexpr (!kSkipR) {
         const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r, off, st.span_bytes);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, 0);
+        for (int s = 0; s < 4; ++s) d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, kStreamOnce);
     } else {
 #pragma unroll
         for (int s = 0; s < 4; ++s) d.r[s] = 0u;
@@ -191,8 +198,8 @@ __device__ __forceinline__ void load_rows_kv(Raw& d, const Streams& st, int t0, 
     const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(st.v, off, st.span_bytes);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-        d.k[s] = __builtin_amdgcn_raw_buffer_load_b32(rk, voff[s], 0, 0);
-        d.v[s] = __builtin_amdgcn_raw_buffer_load_b32(rv, voff[s], 0, 0);
+        d.k[s] = __builtin_amdgcn_raw_buffer_load_b32(rk, voff[s], 0, kStreamOnce);
+        d.v[s] = __builtin_amdgcn_raw_buffer_load_b32(rv, voff[s], 0, kStreamOnce);
     }
 }
 
@@ -455,7 +462,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             const int cc = c < 0 ? 0 : c;                                  // unconditional: exact wait counts
             const long long off = static_cast<long long>(cc) * kChunk * st.row_bytes;
             up_raw = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(
-                                                    chunk_rsrc(up_base, off, st.span_bytes), up_voff, 0, 0));
+                                                    chunk_rsrc(up_base, off, st.span_bytes), up_voff, 0, kStreamOnce));
         }
     };
     auto store_rows = [&](int c) {
@@ -473,20 +480,20 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                     q1.z += bf16_lo(up_raw[3]); q1.w += bf16_hi(up_raw[3]);
                 }
                 if constexpr (kOutF32) {
-                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(a.out) + e);
-                    dst[0] = q0;
-                    dst[1] = q1;
+                    float* dst = static_cast<float*>(a.out) + e;
+                    store_once(dst, __builtin_bit_cast(uint4v, q0));
+                    store_once(dst + 4, __builtin_bit_cast(uint4v, q1));
                 } else {
-                    uint4 q;
+                    uint4v q;
                     q.x = bf16_bits(q0.x) | (static_cast<unsigned>(bf16_bits(q0.y)) << 16);
                     q.y = bf16_bits(q0.z) | (static_cast<unsigned>(bf16_bits(q0.w)) << 16);
                     q.z = bf16_bits(q1.x) | (static_cast<unsigned>(bf16_bits(q1.y)) << 16);
                     q.w = bf16_bits(q1.z) | (static_cast<unsigned>(bf16_bits(q1.w)) << 16);
-                    *reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.out) + e) = q;
+                    store_once(static_cast<unsigned short*>(a.out) + e, q);
                 }
             } else {
-                const uint4 q = *reinterpret_cast<const uint4*>(lds + kO + (srow * kORowBf16 + scol) * 2);
-                *reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.out) + e) = q;
+                const uint4v q = *reinterpret_cast<const uint4v*>(lds + kO + (srow * kORowBf16 + scol) * 2);
+                store_once(static_cast<unsigned short*>(a.out) + e, q);
             }
         }
     };

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(64) void recurrent_kernel(Args a) {
     if (a.state_in) {
         const float* s0 = a.state_in + static_cast<long long>(unit) * N * N;
 #pragma unroll
-        for (int i = 0; i < N; ++i) S[i] = s0[i * N + j];
+        for (int i = 0; i < N; ++i) S[i] = __builtin_nontemporal_load(&s0[i * N + j]);   // streamed once
     } else {
 #pragma unroll
         for (int i = 0; i < N; ++i) S[i] = 0.f;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(64) void recurrent_kernel(Args a) {
     if (a.state_out) {
         float* so = a.state_out + static_cast<long long>(unit) * N * N;
 #pragma unroll
-        for (int i = 0; i < N; ++i) so[i * N + j] = S[i];
+        for (int i = 0; i < N; ++i) __builtin_nontemporal_store(S[i], &so[i * N + j]);
     }
 }
 
