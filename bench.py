@@ -25,9 +25,9 @@ MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 MFMA
 # scaled by the same counter's reading for a plain copy kernel); see profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # FETCH_SIZE (KiB) x 2.0 (copy calibration) + WRITE_SIZE (KiB) x 1.0
-    "config2:wkv6_prefill_bf16": int(262276 * 1024 * 2.0 + 135168 * 1024 * 1.0),
-    "config2:wkv6_finch_c2_prefill_bf16": int(327823 * 1024 * 2.0 + 135168 * 1024 * 1.0),
-    "config2:wkv6_decode_bf16": int(270381 * 1024 * 2.0 + 528384 * 1024 * 1.0),
+    "config2:wkv6_prefill_bf16": int(262260 * 1024 * 2.0 + 135168 * 1024 * 1.0),
+    "config2:wkv6_finch_c2_prefill_bf16": int(327806 * 1024 * 2.0 + 135168 * 1024 * 1.0),
+    "config2:wkv6_decode_bf16": int(270381 * 1024 * 2.0 + 528416 * 1024 * 1.0),
     "config2:wkv6_key_compress_bf16": int(67636 * 1024 * 2.0 + 8192 * 1024 * 1.0),
 }
 
