@@ -171,7 +171,7 @@ int wkv6_finch_c2_prefill_bf16_split(int B, int T, int H, int N,
  * and updated in place (required, not NULL).  Token-by-token fp32 kernel, no fp16 operands, no
  * value-range limit.
  * wkv6_append_bf16: arguments exactly as wkv6_prefill_bf16 (state_in may equal state_out); the
- * library picks the token-by-token kernel for short T (at most 16 tokens) and the chunked
+ * library picks the token-by-token kernel for very short T (at most 6 tokens) and the chunked
  * kernel above that.  Results of the two kernels differ by rounding only, both within the
  * stated tolerance.
  * The finch_c2 variants take kbar and uprime instead of k and u (see wkv6_finch_c2_prefill_bf16).

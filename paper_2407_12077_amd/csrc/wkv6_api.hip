@@ -13,9 +13,10 @@ enum class Path { kChunked, kRecurrent, kBySize };
 
 // Sequences at most this long go to the token-by-token kernel when the caller leaves the
 // choice to the library (append / decode shapes): with thousands of (batch, head) units and
-// a few tokens each the work is streaming the state once, and the chunked kernel's pipeline
-// of five windows per workgroup never fills.  Measured crossover on MI355X: about 20 tokens.
-constexpr int kRecurrentMaxTokens = 16;
+// a few tokens each the work is streaming the state once.  Measured crossover on MI355X with
+// 8192 units: about 8 tokens (the chunked kernel runs the units of a workgroup back to back, one
+// window each at these lengths).
+constexpr int kRecurrentMaxTokens = 6;
 
 // `uprime` selects the form: nullptr = Finch (bonus u), otherwise Finch-C2 (u unused, may be null).
 int run(int B, int T, int H, int N, const void* r, const void* k, const void* v, const void* x,
@@ -45,7 +46,7 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     a.uprime = finch_c2 ? uprime : nullptr;
     a.state_in = state_in; a.out = out; a.state_out = state_out;
     a.batch_stride = batch_stride;
-    a.segs = 1; a.T_last = T; a.seg_stride = 0; a.decay_out = nullptr;
+    a.segs = 1; a.T_last = T; a.seg_stride = 0; a.decay_out = nullptr; a.unit_stride = 0;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;
@@ -261,7 +262,7 @@ int run_split(int B, int T, int H, int N, const void* r, const void* k, const vo
     a.finch_c2 = finch_c2;
     a.uprime = finch_c2 ? uprime : nullptr;
     a.batch_stride = static_cast<long long>(T) * H * N;
-    a.segs = p.segs; a.T_last = p.last_len;
+    a.segs = p.segs; a.T_last = p.last_len; a.unit_stride = 0;
     a.seg_stride = static_cast<long long>(p.seg_len) * H * N;
     // pass 1: every segment from a zero state, no output: its local state and total decay
     a.state_in = nullptr; a.out = nullptr; a.state_out = seg_state; a.decay_out = seg_decay;

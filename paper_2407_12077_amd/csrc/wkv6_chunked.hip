@@ -177,13 +177,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const char* base, l
 // A chunk's loads are issued in two halves (x and r; k and v) so that two different phases can
 // share the cost of issuing them.
 template <bool kSkipR>
-__device__ __forceinline__ void load_rows_xr(Raw& d, const Streams& st, int t0, const int (&voff)[4]) {
+__device__ __forceinline__ void load_rows_xr(Raw& d, const Streams& st, long long unit_bytes, int t0,
+                                             const int (&voff)[4]) {
     const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
-    const __amdgpu_buffer_rsrc_t rx = chunk_rsrc(st.x, off, st.span_bytes);
+    const __amdgpu_buffer_rsrc_t rx = chunk_rsrc(st.x + unit_bytes, off, st.span_bytes);
 #pragma unroll
     for (int s = 0; s < 4; ++s) d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, kStreamOnce);
     if constexpr (!kSkipR) {
-        const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r, off, st.span_bytes);
+        const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r + unit_bytes, off, st.span_bytes);
 #pragma unroll
         for (int s = 0; s < 4; ++s) d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, kStreamOnce);
     } else {
@@ -192,16 +193,56 @@ __device__ __forceinline__ void load_rows_xr(Raw& d, const Streams& st, int t0, 
     }
 }
 
-__device__ __forceinline__ void load_rows_kv(Raw& d, const Streams& st, int t0, const int (&voff)[4]) {
+__device__ __forceinline__ void load_rows_kv(Raw& d, const Streams& st, long long unit_bytes, int t0,
+                                             const int (&voff)[4]) {
     const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
-    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(st.k, off, st.span_bytes);
-    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(st.v, off, st.span_bytes);
+    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(st.k + unit_bytes, off, st.span_bytes);
+    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(st.v + unit_bytes, off, st.span_bytes);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         d.k[s] = __builtin_amdgcn_raw_buffer_load_b32(rk, voff[s], 0, kStreamOnce);
         d.v[s] = __builtin_amdgcn_raw_buffer_load_b32(rv, voff[s], 0, kStreamOnce);
     }
 }
+
+// The units (batch, head) of one workgroup.  A workgroup keeps its pipeline running across unit
+// boundaries: its chunks form one sequence, unit after unit, and only the state (consumers) and
+// the base addresses change at a boundary, so short sequences do not pay the fill and drain of
+// the pipeline once per unit.  All units of a workgroup share the head (the stride between them
+// is a multiple of H), have the same length T, and lie `step` elements apart.
+struct Units {
+    int first;            // unit index of the first one: selects state_in / state_out / decay_out
+    int stride;           // unit index stride
+    int count;            // how many
+    int nchunks;          // chunks per unit
+    long long base0;      // element offset of the first unit's token 0 in r,k,v,x,out
+    long long step;       // element offset between consecutive units of this workgroup
+};
+
+// Position in the workgroup's chunk sequence: unit ui, chunk c of it.  Advanced without
+// divisions; c < 0 (before the start) and ui >= count (past the end) mean "no chunk".
+// With a single unit per workgroup (kMulti false) ui stays 0 and "past the end" is c >= nchunks.
+template <bool kMulti>
+struct Cursor {
+    int ui, c;
+    __device__ __forceinline__ void advance(int by, int nchunks) {
+        c += by;
+        if constexpr (kMulti) {
+            while (c >= nchunks) {
+                c -= nchunks;
+                ++ui;
+            }
+        }
+    }
+    __device__ __forceinline__ bool live(const Units& un) const {
+        if constexpr (kMulti) return ui < un.count;
+        return c < un.nchunks;
+    }
+    __device__ __forceinline__ long long unit_elems(const Units& un) const {
+        if constexpr (kMulti) return ui * un.step;
+        return 0;
+    }
+};
 
 // What a producer thread carries from phase D (where it digests the raw inputs of its chunk)
 // to phase T (where the other groups' decay totals are known and the tiles are written).
@@ -214,9 +255,9 @@ struct Prep {
 // ------------------------------------------------------------------------------------------
 // Producer waves: group pg (0..2) = chunk index mod 3, wq = wave inside the group
 // ------------------------------------------------------------------------------------------
-template <int kMode, bool kC2>
+template <int kMode, bool kC2, bool kMulti>
 __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, int pg, int wq, int h,
-                                         long long unit_base, long long tok_stride, int T, int nchunks) {
+                                         const Units& un, long long tok_stride, int T) {
     constexpr bool kOutF32 = kMode == 1;
     constexpr bool kStateOnly = kMode == 2;
     constexpr bool kStageF32 = kOutF32 || kC2;   // staging precision of the finished rows
@@ -233,10 +274,10 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     const unsigned hu = kC2 ? 0u : pack_h2(a.u[h * kHeadSize + 2 * cp], a.u[h * kHeadSize + 2 * cp + 1]);
 
     Streams st;
-    st.r = static_cast<const char*>(a.r) + unit_base * 2;
-    st.k = static_cast<const char*>(a.k) + unit_base * 2;
-    st.v = static_cast<const char*>(a.v) + unit_base * 2;
-    st.x = static_cast<const char*>(a.x) + unit_base * 2;
+    st.r = static_cast<const char*>(a.r) + un.base0 * 2;
+    st.k = static_cast<const char*>(a.k) + un.base0 * 2;
+    st.v = static_cast<const char*>(a.v) + un.base0 * 2;
+    st.x = static_cast<const char*>(a.x) + un.base0 * 2;
     st.row_bytes = tok_stride * 2;
     st.span_bytes = static_cast<long long>(T - 1) * st.row_bytes + kHeadSize * 2;
     int voff[4];                                   // byte offsets of this thread's 4 token rows
@@ -264,8 +305,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 
     // Phase D.  Digest the raw inputs in `cur` (chunk c): decays, their products inside
     // the thread's 4-token group (published in G), and every operand that needs nothing else.
-    auto digest = [&](int c, Raw& cur) {
-        char* lds = lds_all + (c & 1) * kBuf;
+    auto digest = [&](int g, int c, Raw& cur) {     // g: position in the sequence, c: chunk of its unit
+        char* lds = lds_all + (g & 1) * kBuf;
         const int t0 = c * kChunk;
         if (t0 + kChunk > T) {
             // last, partial chunk: tokens past the end were read as zeros; give them w = 1
@@ -456,20 +497,25 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     const int scol = 8 * (gtid & 7);             // first of its 8 channels
     [[maybe_unused]] uint4v up_raw = {0u, 0u, 0u, 0u};
     [[maybe_unused]] const int up_voff = static_cast<int>(srow * st.row_bytes + scol * 2);
-    [[maybe_unused]] const char* up_base = kC2 ? static_cast<const char*>(a.uprime) + unit_base * 2 : nullptr;
-    auto load_uprime = [&](int c) {
+    [[maybe_unused]] const char* up_base = kC2 ? static_cast<const char*>(a.uprime) + un.base0 * 2 : nullptr;
+    auto load_uprime = [&](const Cursor<kMulti>& at) {
         if constexpr (kC2 && !kStateOnly) {
-            const int cc = c < 0 ? 0 : c;                                  // unconditional: exact wait counts
+            // unconditional (exact wait counts): before the start it re-reads chunk 0, past the
+            // end the descriptor is empty
+            const int cc = at.c < 0 ? 0 : at.c;
+            const bool live = at.c < 0 || at.live(un);
             const long long off = static_cast<long long>(cc) * kChunk * st.row_bytes;
             up_raw = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(
-                                                    chunk_rsrc(up_base, off, st.span_bytes), up_voff, 0, kStreamOnce));
+                                                    chunk_rsrc(up_base + (live ? at.unit_elems(un) * 2 : 0), off,
+                                                               live ? st.span_bytes : 0),
+                                                    up_voff, 0, kStreamOnce));
         }
     };
-    auto store_rows = [&](int c) {
-        const char* lds = lds_all + (c & 1) * kBuf;
-        const int t = c * kChunk + srow;
+    auto store_rows = [&](int g, const Cursor<kMulti>& at) {   // g: position in the sequence (LDS parity)
+        const char* lds = lds_all + (g & 1) * kBuf;
+        const int t = at.c * kChunk + srow;
         if (t < T) {
-            const long long e = unit_base + static_cast<long long>(t) * tok_stride + scol;
+            const long long e = un.base0 + at.unit_elems(un) + static_cast<long long>(t) * tok_stride + scol;
             if constexpr (kStageF32) {
                 const float4* src = reinterpret_cast<const float4*>(lds + kO + (srow * kORowF32 + scol) * 4);
                 float4 q0 = src[0], q1 = src[1];
@@ -498,51 +544,71 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         }
     };
 
-    // A group spends three consecutive windows on each of its chunks c = pg, pg+3, ...:
-    //   window c    phase D: decays and group products of chunk c from one of two raw register
-    //               sets, then the HBM loads of x and r of the group's chunk after next (c+6) into
+    // A group spends three consecutive windows on each of its chunks g = pg, pg+3, ... of the
+    // workgroup's chunk sequence:
+    //   window g    phase D: decays and group products of chunk g from one of two raw register
+    //               sets, then the HBM loads of x and r of the group's chunk after next (g+6) into
     //               the same set (k and v follow in phase S); they stay in flight for four to six
     //               windows.  Issued unconditionally: past the end the descriptor is empty and the
     //               loads return zeros without touching memory.
-    //   window c+1  phase T: multipliers from all groups' decay totals, every operand tile.
-    //   window c+2  phase S: score MFMAs, and the finished output rows of chunk c-2.
+    //   window g+1  phase T: multipliers from all groups' decay totals, every operand tile.
+    //   window g+2  phase S: score MFMAs, and the finished output rows of chunk g-2.
     // The three groups are one window apart, so every window sees one group in each phase
     // next to the consumers: vector-ALU, LDS and matrix-core work of different chunks overlap.
-    const int nwin = (nchunks + 6) / 3 * 3;
+    const int total = un.count * un.nchunks;
+    const int nwin = (total + 6) / 3 * 3;
+    Cursor<kMulti> cur{0, 0}, ld{0, 0}, stc{0, pg - 2};      // chunk g, chunk g+6 (loads), chunk g-2 (stores)
+    cur.advance(pg, un.nchunks);
+    ld.advance(pg, un.nchunks);
+    stc.advance(0, un.nchunks);
+    auto fetch_xr = [&](Raw& buf, const Cursor<kMulti>& at) {
+        const bool live = at.live(un);                // uniform; dead: offset past the span = empty descriptor
+        load_rows_xr<kStateOnly>(buf, st, live ? at.unit_elems(un) * 2 : 0, live ? at.c * kChunk : T + kChunk, voff);
+    };
+    auto fetch_kv = [&](Raw& buf, const Cursor<kMulti>& at) {
+        const bool live = at.live(un);
+        load_rows_kv(buf, st, live ? at.unit_elems(un) * 2 : 0, live ? at.c * kChunk : T + kChunk, voff);
+    };
     // one chunk of this group through its three windows; `buf` holds its raw inputs and is
     // refilled with the group's chunk after next (six chunks ahead) right after the digest
-    auto cycle = [&](int c, Raw& buf) {
-        if (c < nchunks) digest(c, buf);
-        load_uprime(c - 2);                       // older than the chunk loads: waited for first
-        load_rows_xr<kStateOnly>(buf, st, (c + 6) * kChunk, voff);
+    auto cycle = [&](int g, Raw& buf) {
+        const bool live = cur.live(un);
+        if (live) digest(g, cur.c, buf);
+        load_uprime(stc);                         // older than the chunk loads: waited for first
+        fetch_xr(buf, ld);
         __syncthreads();                                                        // window barrier
-        if (c < nchunks) write_tiles(c);
+        if (live) write_tiles(g);
         __syncthreads();                                                        // window barrier
         if constexpr (!kStateOnly) {
-            if (c < nchunks) scores(c);
-            if (c >= 2 && c - 2 < nchunks) store_rows(c - 2);
+            if (live) scores(g);
+            if (stc.c >= 0 && stc.live(un)) store_rows(g - 2, stc);
         }
-        load_rows_kv(buf, st, (c + 6) * kChunk, voff);    // the other half, from the phase with slack
+        fetch_kv(buf, ld);                        // the other half, from the phase with slack
         __syncthreads();                                                        // window barrier
+        cur.advance(3, un.nchunks);
+        ld.advance(3, un.nchunks);
+        stc.advance(3, un.nchunks);
     };
-    load_rows_xr<kStateOnly>(raw_a, st, pg * kChunk, voff);
-    load_rows_kv(raw_a, st, pg * kChunk, voff);
-    load_rows_xr<kStateOnly>(raw_b, st, (pg + 3) * kChunk, voff);
-    load_rows_kv(raw_b, st, (pg + 3) * kChunk, voff);
+    fetch_xr(raw_a, ld);
+    fetch_kv(raw_a, ld);
+    ld.advance(3, un.nchunks);
+    fetch_xr(raw_b, ld);
+    fetch_kv(raw_b, ld);
+    ld.advance(3, un.nchunks);                    // now six chunks ahead of `cur`
     __syncthreads();                                                            // start barrier
     int done = 0;                                                               // windows passed
     for (; done < pg; ++done) {
         __syncthreads();                                                        // window barrier
     }
-    int c = pg;
+    int g = pg;
 #pragma clang loop unroll(disable)
-    for (; c + 5 < nwin; c += 6) {
-        cycle(c, raw_a);
-        cycle(c + 3, raw_b);
+    for (; g + 5 < nwin; g += 6) {
+        cycle(g, raw_a);
+        cycle(g + 3, raw_b);
         done += 6;
     }
-    if (c + 2 < nwin) {
-        cycle(c, raw_a);
+    if (g + 2 < nwin) {
+        cycle(g, raw_a);
         done += 3;
     }
     for (; done < nwin; ++done) {
@@ -553,8 +619,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 // ------------------------------------------------------------------------------------------
 // Consumer waves
 // ------------------------------------------------------------------------------------------
-template <int kMode, bool kC2>
-__device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane, int cw, int unit, int nchunks) {
+template <int kMode, bool kC2, bool kMulti>
+__device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane, int cw, const Units& un) {
     constexpr bool kOutF32 = kMode == 1;
     constexpr bool kStateOnly = kMode == 2;
     const int l16 = lane & 15;
@@ -563,18 +629,22 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
     // the consumers carry the only sequential chain: let the SIMD arbiter prefer them
     __builtin_amdgcn_s_setprio(3);
 
-    // S[nb][e] = state[n = 16nb + 4g4 + e][j]
-    float4v S[4];
-    if (a.state_in) {
-        const float* s0 = a.state_in + static_cast<long long>(unit) * 4096;
+    // S[nb][e] = state[n = 16nb + 4g4 + e][j]; Snext: the state entering the workgroup's next
+    // unit, fetched while the current unit is still being processed
+    float4v S[4], Snext[4];
+    auto fetch_state = [&](float4v (&dst)[4], int ui) {
+        if (a.state_in && ui < un.count) {
+            const float* s0 = a.state_in + (static_cast<long long>(un.first) + static_cast<long long>(ui) * un.stride) * 4096;
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+            for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) S[nb][e] = s0[(16 * nb + 4 * g4 + e) * 64 + j];
-    } else {
+                for (int e = 0; e < 4; ++e) dst[nb][e] = s0[(16 * nb + 4 * g4 + e) * 64 + j];
+        } else {
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) S[nb] = float4v{0.f, 0.f, 0.f, 0.f};
-    }
+            for (int nb = 0; nb < 4; ++nb) dst[nb] = float4v{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    fetch_state(Snext, 0);
 
     float dtot = 1.f;   // product of all decays so far, key channel `lane` (only with decay_out)
     float4v o[2];       // output rows of the chunk whose state chain ran last: 2 t-blocks x 4 rows
@@ -584,10 +654,12 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
     const int tr_lane = (8 * g4 + (l16 >> 2)) * kRow + 8 * (l16 & 3);
 
     __syncthreads();                                                            // start barrier
-    const int nwin = (nchunks + 6) / 3 * 3;
+    const int total = un.count * un.nchunks;
+    const int nwin = (total + 6) / 3 * 3;
+    Cursor<kMulti> at{0, 0};                         // chunk n-2 of the sequence: the state chain's
 #pragma clang loop unroll(disable)
     for (int n = 0; n < nwin; ++n) {
-        if (!kStateOnly && n >= 3 && n - 3 < nchunks) {
+        if (!kStateOnly && n >= 3 && n - 3 < total) {
             // chunk n-3: o += A V (two partial score tiles), then stage for the producers' stores
             char* lds = lds_all + ((n - 3) & 1) * kBuf;
 #pragma unroll
@@ -607,9 +679,16 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
                 }
             }
         }
-        if (n >= 2 && n - 2 < nchunks) {
+        if (n >= 2 && n - 2 < total) {
             // chunk n-2: the state chain
             const char* lds = lds_all + (n & 1) * kBuf;
+            if (at.c == 0) {
+                // a unit begins: take its entering state, start fetching the next unit's
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) S[nb] = Snext[nb];
+                fetch_state(Snext, at.ui + 1);
+                dtot = 1.f;
+            }
             // inter-chunk read: o[t][j] = sum_n (r_t W(t,-1))[n] S[n][j]; the state registers,
             // rounded to fp16, are the B operand (k-slot order = the r tile's column permutation)
             if constexpr (!kStateOnly) {
@@ -642,21 +721,25 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
                 const half8 kt = lds_read_tr8(lds, kKT + tr_lane + 32 * nb);
                 S[nb] = mfma(kt, vt, S[nb]);
             }
+            if (at.c == un.nchunks - 1) {
+                // the unit ends: its final state and, if asked for, its total decay
+                const long long unit = static_cast<long long>(un.first) + static_cast<long long>(at.ui) * un.stride;
+                if (a.state_out) {
+                    float* so = a.state_out + unit * 4096;
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) so[(16 * nb + 4 * g4 + e) * 64 + j] = S[nb][e];
+                }
+                if (a.decay_out && cw == 0) a.decay_out[unit * kHeadSize + lane] = dtot;
+            }
+            at.advance(1, un.nchunks);
         }
         __syncthreads();                                                        // window barrier
     }
-
-    if (a.state_out) {
-        float* so = a.state_out + static_cast<long long>(unit) * 4096;
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) so[(16 * nb + 4 * g4 + e) * 64 + j] = S[nb][e];
-    }
-    if (a.decay_out && cw == 0) a.decay_out[static_cast<long long>(unit) * kHeadSize + lane] = dtot;
 }
 
-template <int kMode, bool kC2>
+template <int kMode, bool kC2, bool kMulti>
 __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     // MODE.FP16_OVFL = 1 (hwreg id 1, bit 23, one bit): fp16 results that overflow, conversions
@@ -675,11 +758,24 @@ __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
                                 static_cast<long long>(seg) * a.seg_stride +
                                 static_cast<long long>(h) * kHeadSize;
     const int T = (seg == a.segs - 1) ? a.T_last : a.T;
-    const int nchunks = (T + kChunk - 1) / kChunk;
+    // The workgroup's units: this one and, when the launch gave a stride (a multiple of H, whole
+    // sequences only), every stride-th unit after it: same head, batch index advancing.
+    Units un;
+    un.first = unit;
+    un.stride = a.unit_stride;
+    un.count = 1;
+    un.nchunks = (T + kChunk - 1) / kChunk;
+    un.base0 = unit_base;
+    un.step = 0;
+    if constexpr (kMulti) {
+        const long long total = static_cast<long long>(a.B) * a.H;
+        un.count = static_cast<int>((total - unit + a.unit_stride - 1) / a.unit_stride);
+        un.step = static_cast<long long>(a.unit_stride / a.H) * a.batch_stride;
+    }
     if (wid < 4 * kProducerGroups)
-        producer<kMode, kC2>(a, lds, tid, wid >> 2, wid & 3, h, unit_base, tok_stride, T, nchunks);
+        producer<kMode, kC2, kMulti>(a, lds, tid, wid >> 2, wid & 3, h, un, tok_stride, T);
     else
-        consumer<kMode, kC2>(a, lds, tid & 63, wid - 4 * kProducerGroups, unit, nchunks);
+        consumer<kMode, kC2, kMulti>(a, lds, tid & 63, wid - 4 * kProducerGroups, un);
 }
 
 // Sequential fold over the segments of one (batch, head): 256 threads x 16 state entries.
@@ -719,14 +815,34 @@ __global__ __launch_bounds__(256) void combine_kernel(int H, int segs, const flo
     }
 }
 
+// Compute units of the MI355X: with more (batch, head) units than this, each workgroup takes
+// several of them back to back.
+constexpr int kComputeUnits = 256;
+
 template <int kMode, bool kC2>
-hipError_t launch_mode(const Args& a, hipStream_t stream) {
-    const dim3 grid(static_cast<unsigned>(a.B) * static_cast<unsigned>(a.segs) * static_cast<unsigned>(a.H));
-    const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunked_kernel<kMode, kC2>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL((chunked_kernel<kMode, kC2>), grid, dim3(kThreads), kLdsBytes, stream, a);
-    return hipGetLastError();
+hipError_t launch_mode(const Args& args, hipStream_t stream) {
+    Args a = args;
+    long long units = static_cast<long long>(a.B) * a.segs * a.H;
+    a.unit_stride = 0;
+    if (a.segs == 1 && a.H <= kComputeUnits) {
+        const int per_round = a.H * (kComputeUnits / a.H);       // a multiple of H: the head stays fixed
+        if (units > per_round) {
+            a.unit_stride = per_round;
+            units = per_round;
+        }
+    }
+    const dim3 grid(static_cast<unsigned>(units));
+    auto go = [&](auto kernel) {
+        const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), kLdsBytes, stream, a);
+        return hipGetLastError();
+    };
+    if constexpr (kMode != 2) {
+        if (a.unit_stride > 0) return go(&chunked_kernel<kMode, kC2, true>);
+    }
+    return go(&chunked_kernel<kMode, kC2, false>);
 }
 
 }  // namespace

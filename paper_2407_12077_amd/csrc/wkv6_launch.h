@@ -29,6 +29,8 @@ struct Args {
     int T_last;
     long long seg_stride;
     float* decay_out;         // may be nullptr; [B*segs][H][N] product of all decays of the unit
+    int unit_stride;          // set by launch_chunked: 0 = one unit per workgroup; otherwise workgroup w
+                              // handles units w, w + unit_stride, ... (a multiple of H, segs == 1 only)
 };
 
 enum class ChunkedMode { kBf16Out, kF32Out, kStateOnly };

@@ -330,3 +330,24 @@ def test_operands_beyond_fp16_range_saturate(gpu_device):
     o_ref, s_ref = wkv6_oracle(**clamped)
     assert 1.0e3 < np.abs(s_ref).max() < 3.0e4
     assert max_norm_err(o, o_ref) <= TOL_BF16 and max_norm_err(s, s_ref) <= TOL_BF16
+
+
+@pytest.mark.parametrize("B,T,H", [(70, 45, 4), (300, 20, 3), (40, 130, 8), (33, 32, 16), (600, 1, 2)])
+def test_many_units_per_workgroup(gpu_device, B, T, H):
+    """More (batch, head) units than compute units: each workgroup runs several units back to
+    back without draining its pipeline; unit counts per workgroup differ by one, lengths ragged."""
+    inp = make_inputs(scaled(CONFIGS[4], B=B, T=T, H=H))
+    check("wkv6_prefill_bf16_f32out", inp, TOL_BF16)
+    o16, s16 = run_entry("wkv6_prefill_bf16", inp, out_dtype=torch.bfloat16)
+    o32, s32 = run_entry("wkv6_prefill_bf16_f32out", inp)
+    assert np.array_equal(o16.astype(np.float32), round_to_bf16(o32.astype(np.float32)))
+    assert np.array_equal(s16, s32)
+
+
+def test_many_units_in_place_state_and_zero_state(gpu_device):
+    inp = make_inputs(scaled(CONFIGS[4], B=90, T=70, H=4))
+    o_ref, s_ref = wkv6_oracle(**inp)
+    o, s = run_entry("wkv6_prefill_bf16_f32out", inp, inplace_state=True)
+    assert max_norm_err(o, o_ref) <= TOL_BF16 and max_norm_err(s, s_ref) <= TOL_BF16
+    inp["state_in"] = None
+    check("wkv6_prefill_bf16_f32out", inp, TOL_BF16)

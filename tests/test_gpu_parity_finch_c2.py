@@ -185,3 +185,12 @@ def test_full_size_config2_sampled_units(gpu_device):
         worst_s = max(worst_s, max_norm_err(s_out[b, h].cpu().numpy(), s_ref[0, 0]))
     print(f"finch-c2 config 2: {len(units)} units, worst err_out={worst_o:.3e} err_state={worst_s:.3e}", flush=True)
     assert worst_o <= TOL_BF16 + BF16_OUT_ROUNDING and worst_s <= TOL_BF16
+
+
+@pytest.mark.parametrize("B,T,H", [(70, 45, 4), (300, 20, 3)])
+def test_many_units_per_workgroup(gpu_device, B, T, H):
+    inp = inputs(scaled(CONFIGS[4], B=B, T=T, H=H))
+    check(inp)
+    o32, _ = run_c2(inp, torch.float32)
+    o16, _ = run_c2(inp, torch.bfloat16)
+    assert np.array_equal(o16.astype(np.float32), round_to_bf16(o32.astype(np.float32)))
