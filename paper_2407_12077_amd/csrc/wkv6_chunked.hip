@@ -1,4 +1,5 @@
-// Chunked WKV6 prefill kernel for gfx950 (MI355X): one workgroup per (batch, head), fp32 state
+// Chunked WKV6 prefill kernel for gfx950 (MI355X): one workgroup per (batch, head) -- or, with
+// more units than compute units, several units back to back per workgroup -- fp32 state
 // carried in MFMA accumulators, every dense contraction on the matrix cores
 // (v_mfma_f32_16x16x32_f16, fp32 accumulation).
 //
@@ -35,8 +36,9 @@
 // In window n: D(chunk n), T(n-1), S(n-2), consumers' state chain on chunk n-2 and A.V on n-3.
 // LDS buffers (tiles, scores, decay totals, output staging) are indexed by chunk parity.
 //
-// Finch-C2 form (template flag): the key is multiplied by (1 - w) in phase D, there is no bonus
-// tile or bonus MFMA, and the second value u' is added to the fp32-staged rows before the store.
+// Finch-C2 form (template flag): the key is multiplied by (1 - w) in phase D, u does not enter
+// the level-1 tiles, the diagonal of the scores is zero, and the second value u' is added to the
+// fp32-staged rows before the store.
 //
 // LDS tiles are [token][channel] fp16 with a 160-byte row stride, the stride at which the
 // 16-byte row reads of MFMA operands run at the full rate of the gfx950 LDS; operands whose
