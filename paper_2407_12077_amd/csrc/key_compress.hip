@@ -227,8 +227,17 @@ __global__ __launch_bounds__(kKcThreads, 2) void key_compress_kernel(KcArgs a) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const long long m0 = static_cast<long long>(blockIdx.x) * kBM;
-    const int n0 = blockIdx.y * kBN;
+    // Block -> tile map.  With more than one column tile (D > 2048) the column tiles of one row tile
+    // must meet in the same L2 so that x comes from HBM once: consecutive block ids go round the
+    // 8 XCDs, so the id is read as (slot, xcd) and the column tiles of a row tile take consecutive
+    // slots of one XCD.
+    const int nct = a.C / kBN;
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const long long row_tile = static_cast<long long>(slot / nct) * 8 + xcd;
+    const long long m0 = row_tile * kBM;
+    const int n0 = (slot % nct) * kBN;
+    if (m0 >= a.M) return;                     // padding of the row tiles to a multiple of 8
     const long long rows_left = a.M - m0;
     const int rows = rows_left < kBM ? static_cast<int>(rows_left) : kBM;
     const int nsteps = a.D / kBK;
@@ -246,7 +255,8 @@ hipError_t launch_key_compress(long long M, int D, const void* x, const void* w,
     KcArgs a;
     a.M = M; a.D = D; a.C = D / 16;
     a.x = x; a.w = w; a.c = c;
-    const dim3 grid(static_cast<unsigned>((M + kBM - 1) / kBM), static_cast<unsigned>(a.C / kBN));
+    const long long row_tiles = (M + kBM - 1) / kBM;
+    const dim3 grid(static_cast<unsigned>((row_tiles + 7) / 8 * 8 * (a.C / kBN)));
     hipError_t err;
     if (out_f32) {
         err = hipFuncSetAttribute(reinterpret_cast<const void*>(&key_compress_kernel<true>),
