@@ -143,7 +143,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over (batch, head) "
-                 "with no communication; see DESIGN.md); use --gpus 1")
+                 "with no communication); use --gpus 1")
 
     import torch
     import paper_2407_12077_amd as wkv

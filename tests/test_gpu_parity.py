@@ -251,7 +251,7 @@ def _unit_slice(inp, b, h):
 
 @pytest.mark.parametrize("cfg_index,n_units", [(2, 12), (3, 3), (4, 48), (5, 6)])
 def test_full_size_config_sampled_units(gpu_device, cfg_index, n_units):
-    """The benchmark's launch configuration at BASELINE size; the oracle recomputes a seeded
+    """The benchmark's launch configuration at full size; the oracle recomputes a seeded
     sample of (batch, head) units in full (every token and the final state of each)."""
     cfg = CONFIGS[cfg_index]
     inp = make_inputs(cfg)
