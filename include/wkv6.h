@@ -197,7 +197,7 @@ int wkv6_finch_c2_append_bf16(int B, int T, int H, int N,
  * and D/16 columns.  A skinny matrix product bound by the one HBM read of x; bf16 operands,
  * fp32 accumulation on the matrix cores, one rounding of the result.
  *   M      tokens (batch x sequence, any M >= 0; 0 is a no-op)
- *   D      model dimension, a multiple of 2048 (other values: WKV6_ERR_UNSUPPORTED)
+ *   D      model dimension, a multiple of 256 up to 65536 (other values: WKV6_ERR_UNSUPPORTED)
  *   x      [M][D]     bf16 device pointer, 16-byte aligned
  *   w_kd   [D][D/16]  bf16, row-major as the paper writes it (x on the left)
  *   c      [M][D/16]  bf16 or fp32 per out_dtype (a wkv6_dtype)

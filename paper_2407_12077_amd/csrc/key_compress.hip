@@ -5,8 +5,8 @@
 // by the HBM read of x; all arithmetic is on the matrix cores (v_mfma_f32_16x16x32_bf16, fp32
 // accumulation, bf16 products are exact in fp32).
 //
-// One workgroup owns 128 tokens x 128 output columns and walks the D axis in steps of 64
-// channels.  Its eight waves split into two roles that meet at one barrier per step:
+// One workgroup owns 128 tokens x 128 output columns (fewer in the last column tile when D/16 is
+// not a multiple of 128) and walks the D axis in steps of 64 channels.  Its eight waves split into two roles that meet at one barrier per step:
 //   waves 4..7  LOADERS: fetch the x tile (128 x 64: full 128-byte row pieces, 8 lanes each) and
 //               the W tile (64 x 128, an L2 hit) of a step two steps ahead into registers with
 //               16-byte loads, and park the tiles of the next step in one of two LDS buffers.
@@ -96,7 +96,8 @@ __device__ __forceinline__ void kc_loader(const KcArgs& a, char* lds, int lt, lo
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         x_voff[p] = static_cast<int>((xr + 32 * p) * x_row_bytes + 16 * xg);
-        w_voff[p] = static_cast<int>((wr + 16 * p) * w_row_bytes + n0 * 2 + 16 * wg);
+        // columns past C (the last column tile may be partial): an offset no descriptor covers
+        w_voff[p] = n0 + 8 * wg < a.C ? static_cast<int>((wr + 16 * p) * w_row_bytes + n0 * 2 + 16 * wg) : 0x7ffffff0;
     }
     const int x_lds = xr * kXRow + 16 * xg;
     const int w_lds = kXTile + wr * kWRow + 16 * wg;
@@ -202,7 +203,7 @@ __device__ __forceinline__ void kc_worker(const KcArgs& a, char* lds, int tid, i
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int row = cr + 32 * p;
-        if (row < rows) {
+        if (row < rows && n0 + 16 * cg < a.C) {
             const float4* src = reinterpret_cast<const float4*>(lds + row * kCRow + cg * 64);
             const float4 q0 = src[0], q1 = src[1], q2 = src[2], q3 = src[3];
             const long long e = (m0 + row) * a.C + n0 + 16 * cg;
@@ -231,7 +232,7 @@ __global__ __launch_bounds__(kKcThreads, 2) void key_compress_kernel(KcArgs a) {
     // must meet in the same L2 so that x comes from HBM once: consecutive block ids go round the
     // 8 XCDs, so the id is read as (slot, xcd) and the column tiles of a row tile take consecutive
     // slots of one XCD.
-    const int nct = a.C / kBN;
+    const int nct = (a.C + kBN - 1) / kBN;
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;
     const long long row_tile = static_cast<long long>(slot / nct) * 8 + xcd;
@@ -256,7 +257,7 @@ hipError_t launch_key_compress(long long M, int D, const void* x, const void* w,
     a.M = M; a.D = D; a.C = D / 16;
     a.x = x; a.w = w; a.c = c;
     const long long row_tiles = (M + kBM - 1) / kBM;
-    const dim3 grid(static_cast<unsigned>((row_tiles + 7) / 8 * 8 * (a.C / kBN)));
+    const dim3 grid(static_cast<unsigned>((row_tiles + 7) / 8 * 8 * ((a.C + kBN - 1) / kBN)));
     hipError_t err;
     if (out_f32) {
         err = hipFuncSetAttribute(reinterpret_cast<const void*>(&key_compress_kernel<true>),

@@ -157,8 +157,8 @@ int wkv6_prefill_bf16_recurrent(int B, int T, int H, int N, const void* r, const
 int wkv6_key_compress_bf16(long long M, int D, const void* x, const void* w_kd, void* c, int out_dtype,
                            void* stream) {
     if (out_dtype != WKV6_DTYPE_BF16 && out_dtype != WKV6_DTYPE_F32) return WKV6_ERR_UNSUPPORTED;
-    if (D < 2048 || D % 2048 != 0 || D > 65536) return WKV6_ERR_UNSUPPORTED;
-    if (M < 0 || ((M + 127) / 128 + 8) * (D / 2048) > 0x7fffffffLL) return WKV6_ERR_SHAPE;   // grid size
+    if (D < 256 || D % 256 != 0 || D > 65536) return WKV6_ERR_UNSUPPORTED;
+    if (M < 0 || ((M + 127) / 128 + 8) * ((D / 16 + 127) / 128) > 0x7fffffffLL) return WKV6_ERR_SHAPE;   // grid size
     if (M == 0) return WKV6_OK;
     if (!x || !w_kd || !c) return WKV6_ERR_NULL;
     if (misaligned(x) || misaligned(w_kd) || misaligned(c)) return WKV6_ERR_ALIGN;

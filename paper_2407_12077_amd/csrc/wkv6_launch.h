@@ -50,7 +50,7 @@ hipError_t launch_combine_segments(int B, int H, int segs, const float* state_in
                                    const float* seg_decay, float* state_out, hipStream_t stream);
 
 // GOLD key compression c = x W: x [M][D] bf16, w [D][D/16] bf16, c [M][D/16] bf16 or fp32.
-// D must be a multiple of 2048 (128 output columns per workgroup).
+// D must be a multiple of 256 (16 output columns per MFMA block, an even number of 64-channel steps).
 hipError_t launch_key_compress(long long M, int D, const void* x, const void* w, void* c, bool out_f32,
                                hipStream_t stream);
 

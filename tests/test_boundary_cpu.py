@@ -91,7 +91,7 @@ def test_decode_and_append_validation():
 
 def test_key_compress_validation():
     f = _raw("wkv6_key_compress_bf16")
-    assert f(4, 1024, A, A, A, 0, None) == 3               # D not a multiple of 2048
+    assert f(4, 1000, A, A, A, 0, None) == 3               # D not a multiple of 256
     assert f(4, 2048, A, A, A, 5, None) == 3               # dtype code
     assert f(-4, 2048, A, A, A, 0, None) == 2
     assert f(4, 2048, A, None, A, 0, None) == 1

@@ -25,7 +25,8 @@ def run(x, w, out_dtype):
     return c.float().cpu().numpy()
 
 
-@pytest.mark.parametrize("M,D", [(1, 2048), (127, 2048), (128, 2048), (129, 2048), (1000, 2048), (300, 4096)])
+@pytest.mark.parametrize("M,D", [(1, 2048), (127, 2048), (128, 2048), (129, 2048), (1000, 2048), (300, 4096), (200, 256),
+                                 (333, 768), (500, 1024), (130, 2304), (1100, 4096)])
 def test_matches_oracle(gpu_device, M, D):
     x, w = make_key_compress_inputs(M, D, seed=500 + M)
     ref = key_compress_oracle(x, w)
@@ -50,7 +51,7 @@ def test_empty_and_validation(gpu_device):
     w = torch.zeros((2048, 128), dtype=torch.bfloat16, device="cuda")
     c = torch.zeros((4, 128), dtype=torch.bfloat16, device="cuda")
     wkv.wkv6_key_compress_bf16(0, 2048, None, None, None, wkv.WKV6_DTYPE_BF16)
-    for args, status in [((4, 1024, z, w, c, 0), 3), ((4, 2048, z, w, c, 9), 3), ((4, 2048, None, w, c, 0), 1),
+    for args, status in [((4, 1000, z, w, c, 0), 3), ((4, 2048, z, w, c, 9), 3), ((4, 2048, None, w, c, 0), 1),
                          ((-1, 2048, z, w, c, 0), 2)]:
         with pytest.raises(wkv.Wkv6Error) as e:
             wkv.wkv6_key_compress_bf16(*args)
