@@ -332,7 +332,7 @@ def test_operands_beyond_fp16_range_saturate(gpu_device):
     assert max_norm_err(o, o_ref) <= TOL_BF16 and max_norm_err(s, s_ref) <= TOL_BF16
 
 
-@pytest.mark.parametrize("B,T,H", [(70, 45, 4), (300, 20, 3), (40, 130, 8), (33, 32, 16), (600, 1, 2), (5, 40, 96),
+@pytest.mark.parametrize("B,T,H", [(70, 45, 4), (300, 20, 3), (40, 130, 8), (33, 32, 16), (600, 1, 2), (5, 40, 96), (12, 70, 64),
                                    (1, 40, 260), (2, 33, 260)])
 def test_many_units_per_workgroup(gpu_device, B, T, H):
     """More (batch, head) units than compute units: each workgroup runs several units back to
