@@ -550,7 +550,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // workgroup's chunk sequence:
     //   window g    phase D: decays and group products of chunk g from one of two raw register
     //               sets, then the HBM loads of x and r of the group's chunk after next (g+6) into
-    //               the same set (k and v follow in phase S); they stay in flight for four to six
+    //               the same set (k and v follow in phase T); they stay in flight for four to six
     //               windows.  Issued unconditionally: past the end the descriptor is empty and the
     //               loads return zeros without touching memory.
     //   window g+1  phase T: multipliers from all groups' decay totals, every operand tile.
@@ -580,12 +580,12 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         fetch_xr(buf, ld);
         __syncthreads();                                                        // window barrier
         if (live) write_tiles(g);
+        fetch_kv(buf, ld);                        // the other half: issued a window later, measured best here
         __syncthreads();                                                        // window barrier
         if constexpr (!kStateOnly) {
             if (live) scores(g);
             if (stc.c >= 0 && stc.live(un)) store_rows(g - 2, stc);
         }
-        fetch_kv(buf, ld);                        // the other half, from the phase with slack
         __syncthreads();                                                        // window barrier
         cur.advance(3, un.nchunks);
         ld.advance(3, un.nchunks);
