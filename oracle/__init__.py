@@ -14,6 +14,10 @@ and never imports it.
 ``key_compress_oracle``
                   the GOLD key compression c_t = x_t W^KD as three plain loops
                   (``key_compress_oracle.c``).
+``layernorm_heads_numpy`` / ``head_moments_numpy``
+                  the LayerNorm over the concatenated heads of the Finch-C2 output equation and
+                  the per-head partial moments it can be combined from (``layernorm_numpy.py``).
 """
 from .cbuild import build_oracle, finch_c2_oracle, key_compress_oracle, wkv6_oracle  # noqa: F401
+from .layernorm_numpy import head_moments_numpy, layernorm_heads_numpy  # noqa: F401
 from .wkv6_numpy import finch_c2_numpy, wkv6_numpy  # noqa: F401
