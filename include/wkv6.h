@@ -162,6 +162,38 @@ int wkv6_finch_c2_prefill_bf16_split(int B, int T, int H, int N,
                                      void *workspace, long long workspace_bytes, void *stream);
 
 /*
+ * Finch-C2 prefill that also emits the partial statistics of the LayerNorm that follows it
+ * (paper: Method, "Finch-C2 Time Mixing", output equation: one LayerNorm over the concatenation
+ * of all heads' read-outs of a token, then the output projection).  A token's heads are
+ * computed by different workgroups, so the kernel writes, per (batch, head, token),
+ *
+ *     moments[b][h][t][0] = sum_n o[b][t][h][n]
+ *     moments[b][h][t][1] = sum_n (o[b][t][h][n] - moments[b][h][t][0] / N)^2
+ *
+ * of the fp32 read-out values before their rounding to bf16 ([B][H][T][2] fp32, device, 16-byte
+ * aligned, 8 bytes per token-head: about 1 % of the call's traffic).  wkv6_layernorm_finalize
+ * folds them into each token's mean and 1/sqrt(variance + eps); with these two numbers per
+ * token the normalisation becomes a row scaling and a rank-one correction in the epilogue of
+ * the projection GEMM, LayerNorm(o_t) W = rstd_t (o_t (diag(gamma) W)) - rstd_t mean_t
+ * (gamma W) + beta W, and no separate pass over `out` is needed.
+ * Everything else is as for wkv6_finch_c2_prefill_bf16 (always the chunked kernel; `moments` must
+ * not be NULL when T > 0; T == 0 writes nothing to it).
+ */
+int wkv6_finch_c2_prefill_bf16_moments(int B, int T, int H, int N,
+                                       const void *r, const void *kbar, const void *v, const void *x,
+                                       const void *uprime, const float *state_in,
+                                       void *out, float *moments, float *state_out, void *stream);
+
+/*
+ * mean_rstd[b][t] = (mean, 1/sqrt(var + eps)) of the H*N read-out values of token (b, t), var
+ * dividing by H*N, from `moments` as written above ([B][T][2] fp32, device, 16-byte aligned).
+ * eps >= 0; the paper names the operator only, so eps is the caller's (1e-5 is the usual
+ * default).  Errors as elsewhere; B == 0 or T == 0 is a no-op.
+ */
+int wkv6_layernorm_finalize(int B, int T, int H, int N, const float *moments, float eps,
+                            float *mean_rstd, void *stream);
+
+/*
  * Serving shapes: the same recurrence for one token (decode) or a few tokens (append) per
  * sequence and many sequences, where the cost is streaming each fp32 state through once
  * (paper: GoldFinch pre-fill is an RNN pass, so a cache is extended token by token with the

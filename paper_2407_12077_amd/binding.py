@@ -19,7 +19,8 @@ EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_s
            "wkv6_prefill_f32", "wkv6_prefill_bf16_recurrent", "wkv6_prefill_bf16_split",
            "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_finch_c2_prefill_bf16",
            "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_strided",
-           "wkv6_finch_c2_prefill_bf16_split",
+           "wkv6_finch_c2_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16_moments",
+           "wkv6_layernorm_finalize",
            "wkv6_decode_bf16", "wkv6_finch_c2_decode_bf16", "wkv6_append_bf16",
            "wkv6_finch_c2_append_bf16", "wkv6_key_compress_bf16", "wkv6_status_string", "wkv6_version")
 
@@ -57,6 +58,10 @@ def load():
             fn = getattr(lib, name)
             fn.restype = i
             fn.argtypes = [i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.wkv6_finch_c2_prefill_bf16_moments.restype = i
+        lib.wkv6_finch_c2_prefill_bf16_moments.argtypes = [i, i, i, i] + [vp] * 10
+        lib.wkv6_layernorm_finalize.restype = i
+        lib.wkv6_layernorm_finalize.argtypes = [i, i, i, i, vp, ctypes.c_float, vp, vp]
         lib.wkv6_key_compress_bf16.restype = i
         lib.wkv6_key_compress_bf16.argtypes = [ll, i, vp, vp, vp, i, vp]
         lib.wkv6_prefill_bf16_split.restype = i
@@ -157,6 +162,18 @@ def wkv6_finch_c2_prefill_bf16_strided(B, T, H, N, r, kbar, v, x, uprime, state_
                                        batch_stride, out_dtype, stream=None):
     _call("wkv6_finch_c2_prefill_bf16_strided", B, T, H, N, r, kbar, v, x, uprime, state_in, out,
           state_out, stream, ctypes.c_longlong(batch_stride), int(out_dtype))
+
+
+def wkv6_finch_c2_prefill_bf16_moments(B, T, H, N, r, kbar, v, x, uprime, state_in, out, moments, state_out,
+                                       stream=None):
+    _check(load().wkv6_finch_c2_prefill_bf16_moments(
+        B, T, H, N, _ptr(r), _ptr(kbar), _ptr(v), _ptr(x), _ptr(uprime), _ptr(state_in), _ptr(out),
+        _ptr(moments), _ptr(state_out), _stream(stream)))
+
+
+def wkv6_layernorm_finalize(B, T, H, N, moments, eps, mean_rstd, stream=None):
+    _check(load().wkv6_layernorm_finalize(B, T, H, N, _ptr(moments), ctypes.c_float(eps), _ptr(mean_rstd),
+                                          _stream(stream)))
 
 
 def wkv6_append_bf16(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):

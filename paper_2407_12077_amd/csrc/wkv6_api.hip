@@ -22,7 +22,8 @@ constexpr int kRecurrentMaxTokens = 6;
 int run(int B, int T, int H, int N, const void* r, const void* k, const void* v, const void* x,
         const float* u, const float* state_in, void* out, float* state_out,
         long long batch_stride, bool in_bf16, bool out_f32, Path path, void* stream,
-        const void* uprime = nullptr, bool finch_c2 = false) {
+        const void* uprime = nullptr, bool finch_c2 = false, float* moments = nullptr,
+        bool want_moments = false) {
     if (N != wkv6::kHeadSize) return WKV6_ERR_UNSUPPORTED;
     if (B < 0 || T < 0 || H < 1 || H > 262144) return WKV6_ERR_SHAPE;   // 32-bit row offsets in the kernels
     if (!finch_c2 && !u) return WKV6_ERR_NULL;
@@ -38,6 +39,10 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     }
     if (misaligned(u) || misaligned(state_in) || misaligned(state_out)) return WKV6_ERR_ALIGN;
     if (static_cast<long long>(B) * H > 0x7fffffffLL) return WKV6_ERR_SHAPE;
+    if (want_moments && T > 0) {
+        if (!moments) return WKV6_ERR_NULL;
+        if (misaligned(moments)) return WKV6_ERR_ALIGN;
+    }
 
     wkv6::Args a;
     a.B = B; a.T = T; a.H = H;
@@ -47,6 +52,7 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     a.state_in = state_in; a.out = out; a.state_out = state_out;
     a.batch_stride = batch_stride;
     a.segs = 1; a.T_last = T; a.seg_stride = 0; a.decay_out = nullptr; a.unit_stride = 0;
+    a.moments = moments;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;
@@ -54,6 +60,8 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
         err = wkv6::launch_state_passthrough(a, s);
     else if (path == Path::kRecurrent || (path == Path::kBySize && T <= kRecurrentMaxTokens))
         err = wkv6::launch_recurrent(a, in_bf16, in_bf16 && !out_f32, s);
+    else if (want_moments)
+        err = wkv6::launch_chunked(a, wkv6::ChunkedMode::kBf16OutMoments, s);
     else
         err = wkv6::launch_chunked(a, out_f32 ? wkv6::ChunkedMode::kF32Out : wkv6::ChunkedMode::kBf16Out, s);
     return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
@@ -108,6 +116,27 @@ int wkv6_finch_c2_prefill_bf16_strided(int B, int T, int H, int N, const void* r
     if (out_dtype != WKV6_DTYPE_BF16 && out_dtype != WKV6_DTYPE_F32) return WKV6_ERR_UNSUPPORTED;
     return run(B, T, H, N, r, kbar, v, x, nullptr, state_in, out, state_out, batch_stride, true,
                out_dtype == WKV6_DTYPE_F32, Path::kChunked, stream, uprime, true);
+}
+
+int wkv6_finch_c2_prefill_bf16_moments(int B, int T, int H, int N, const void* r, const void* kbar,
+                                       const void* v, const void* x, const void* uprime,
+                                       const float* state_in, void* out, float* moments, float* state_out,
+                                       void* stream) {
+    return run(B, T, H, N, r, kbar, v, x, nullptr, state_in, out, state_out,
+               static_cast<long long>(T) * H * N, true, false, Path::kChunked, stream, uprime, true, moments,
+               true);
+}
+
+int wkv6_layernorm_finalize(int B, int T, int H, int N, const float* moments, float eps, float* mean_rstd,
+                            void* stream) {
+    if (N != wkv6::kHeadSize) return WKV6_ERR_UNSUPPORTED;
+    if (B < 0 || T < 0 || H < 1 || H > 262144 || B > 65535 || !(eps >= 0.f)) return WKV6_ERR_SHAPE;
+    if (B == 0 || T == 0) return WKV6_OK;
+    if (!moments || !mean_rstd) return WKV6_ERR_NULL;
+    if (misaligned(moments) || misaligned(mean_rstd)) return WKV6_ERR_ALIGN;
+    const hipError_t err = wkv6::launch_layernorm_finalize(B, T, H, moments, eps, mean_rstd,
+                                                           static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
 }
 
 int wkv6_append_bf16(int B, int T, int H, int N, const void* r, const void* k, const void* v,
@@ -179,7 +208,7 @@ const char* wkv6_status_string(int status) {
     }
 }
 
-int wkv6_version(void) { return 400; }
+int wkv6_version(void) { return 410; }
 
 }  // extern "C"
 
@@ -262,7 +291,7 @@ int run_split(int B, int T, int H, int N, const void* r, const void* k, const vo
     a.finch_c2 = finch_c2;
     a.uprime = finch_c2 ? uprime : nullptr;
     a.batch_stride = static_cast<long long>(T) * H * N;
-    a.segs = p.segs; a.T_last = p.last_len; a.unit_stride = 0;
+    a.segs = p.segs; a.T_last = p.last_len; a.unit_stride = 0; a.moments = nullptr;
     a.seg_stride = static_cast<long long>(p.seg_len) * H * N;
     // pass 1: every segment from a zero state, no output: its local state and total decay
     a.state_in = nullptr; a.out = nullptr; a.state_out = seg_state; a.decay_out = seg_decay;

@@ -221,6 +221,19 @@ struct Units {
     long long step;       // element offset between consecutive units of this workgroup
 };
 
+// Sum over the 8 lanes of an aligned group of 8 (every lane gets the total): neighbours, pairs,
+// then the mirrored half-row, all as data-parallel-primitive moves inside the vector ALU.
+template <int kCtrl>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row8_sum(float v) {
+    v += dpp_move<0xB1>(v);       // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);       // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);      // row_half_mirror: lane i <-> 7 - i of each 8
+    return v;
+}
+
 // Position in the workgroup's chunk sequence: unit ui, chunk c of it.  Advanced without
 // divisions; c < 0 (before the start) and ui >= count (past the end) mean "no chunk".
 // With a single unit per workgroup (kMulti false) ui stays 0 and "past the end" is c >= nchunks.
@@ -262,6 +275,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                                          const Units& un, long long tok_stride, int T) {
     constexpr bool kOutF32 = kMode == 1;
     constexpr bool kStateOnly = kMode == 2;
+    constexpr bool kMoments = kMode == 3;        // bf16 out plus the per-head LayerNorm partials
     constexpr bool kStageF32 = kOutF32 || kC2;   // staging precision of the finished rows
     const int lane = tid & 63;
     const int gtid = tid & 255;              // thread inside the group
@@ -526,6 +540,27 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                     q0.z += bf16_lo(up_raw[1]); q0.w += bf16_hi(up_raw[1]);
                     q1.x += bf16_lo(up_raw[2]); q1.y += bf16_hi(up_raw[2]);
                     q1.z += bf16_lo(up_raw[3]); q1.w += bf16_hi(up_raw[3]);
+                }
+                if constexpr (kMoments) {
+                    // The 8 threads of a row hold the head's 64 finished values of this token: their
+                    // sum, then the squared deviations from the head's own mean, each folded over
+                    // the 8 lanes; the row's first thread writes the pair.
+                    const float s = row8_sum(((q0.x + q0.y) + (q0.z + q0.w)) + ((q1.x + q1.y) + (q1.z + q1.w)));
+                    const float m = s * (1.f / kHeadSize);
+                    float m2 = (q0.x - m) * (q0.x - m);
+                    m2 = fmaf(q0.y - m, q0.y - m, m2);
+                    m2 = fmaf(q0.z - m, q0.z - m, m2);
+                    m2 = fmaf(q0.w - m, q0.w - m, m2);
+                    m2 = fmaf(q1.x - m, q1.x - m, m2);
+                    m2 = fmaf(q1.y - m, q1.y - m, m2);
+                    m2 = fmaf(q1.z - m, q1.z - m, m2);
+                    m2 = fmaf(q1.w - m, q1.w - m, m2);
+                    m2 = row8_sum(m2);
+                    if (scol == 0) {
+                        long long unit_index = un.first;
+                        if constexpr (kMulti) unit_index += static_cast<long long>(at.ui) * un.stride;
+                        *reinterpret_cast<float2*>(a.moments + (unit_index * T + t) * 2) = make_float2(s, m2);
+                    }
                 }
                 if constexpr (kOutF32) {
                     float* dst = static_cast<float*>(a.out) + e;
@@ -854,7 +889,10 @@ hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream) {
     switch (mode) {
         case ChunkedMode::kBf16Out: return c2 ? launch_mode<0, true>(a, stream) : launch_mode<0, false>(a, stream);
         case ChunkedMode::kF32Out: return c2 ? launch_mode<1, true>(a, stream) : launch_mode<1, false>(a, stream);
-        default: return c2 ? launch_mode<2, true>(a, stream) : launch_mode<2, false>(a, stream);
+        case ChunkedMode::kStateOnly: return c2 ? launch_mode<2, true>(a, stream) : launch_mode<2, false>(a, stream);
+        default:
+            if (!c2 || a.segs != 1 || !a.moments) return hipErrorInvalidValue;
+            return launch_mode<3, true>(a, stream);
     }
 }
 

@@ -29,18 +29,22 @@ struct Args {
     int T_last;
     long long seg_stride;
     float* decay_out;         // may be nullptr; [B*segs][H][N] product of all decays of the unit
+    float* moments;           // kBf16OutMoments only: [B][H][T][2] per (batch, head, token): the sum of
+                              // the head's N output values and their squared deviations from the
+                              // head's own mean (taken before the rounding to bf16)
     int unit_stride;          // set by launch_chunked: 0 = one unit per workgroup; otherwise workgroup w
                               // handles units w, w + unit_stride, ... (a multiple of H, segs == 1 only)
 };
 
-enum class ChunkedMode { kBf16Out, kF32Out, kStateOnly };
+enum class ChunkedMode { kBf16Out, kF32Out, kStateOnly, kBf16OutMoments };
 
 // Token-by-token fp32 kernel; inputs bf16 or fp32 (fp32 inputs: fp32 out, Finch form only);
 // with bf16 inputs the output is fp32 or bf16 and a.finch_c2 selects the form.
 hipError_t launch_recurrent(const Args& a, bool in_bf16, bool out_bf16, hipStream_t stream);
 
 // Chunked matrix-core kernel; inputs bf16, out bf16 or fp32, or (kStateOnly) no output at all:
-// only state_out and decay_out of every unit, from r-independent work.
+// only state_out and decay_out of every unit, from r-independent work.  kBf16OutMoments: bf16 out
+// plus a.moments, Finch-C2 form and segs == 1 only.
 hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream);
 
 // Token-split support: folds the per-segment (decay, local state) pairs of every (batch, head)
@@ -53,6 +57,11 @@ hipError_t launch_combine_segments(int B, int H, int segs, const float* state_in
 // D must be a multiple of 256 (16 output columns per MFMA block, an even number of 64-channel steps).
 hipError_t launch_key_compress(long long M, int D, const void* x, const void* w, void* c, bool out_f32,
                                hipStream_t stream);
+
+// Folds the H per-head (sum, squared deviations) pairs of every token into the token's mean and
+// 1/sqrt(variance + eps) over all H*N channels: moments [B][H][T][2] -> mean_rstd [B][T][2].
+hipError_t launch_layernorm_finalize(int B, int T, int H, const float* moments, float eps, float* mean_rstd,
+                                     hipStream_t stream);
 
 // T == 0: state_out = state_in (or zero).
 hipError_t launch_state_passthrough(const Args& a, hipStream_t stream);
