@@ -17,7 +17,11 @@ and never imports it.
 ``layernorm_heads_numpy`` / ``head_moments_numpy``
                   the LayerNorm over the concatenated heads of the Finch-C2 output equation and
                   the per-head partial moments it can be combined from (``layernorm_numpy.py``).
+``lora_numpy`` / ``decay_logits_numpy``
+                  the low-rank operator lambda + tanh(x A) B and its last factor, the decay logits
+                  from y = tanh(. A) (``decay_lora_numpy.py``).
 """
 from .cbuild import build_oracle, finch_c2_oracle, key_compress_oracle, wkv6_oracle  # noqa: F401
+from .decay_lora_numpy import decay_logits_numpy, lora_numpy  # noqa: F401
 from .layernorm_numpy import head_moments_numpy, layernorm_heads_numpy  # noqa: F401
 from .wkv6_numpy import finch_c2_numpy, wkv6_numpy  # noqa: F401
