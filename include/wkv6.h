@@ -194,6 +194,31 @@ int wkv6_layernorm_finalize(int B, int T, int H, int N, const float *moments, fl
                             float *mean_rstd, void *stream);
 
 /*
+ * Finch-C2 prefill with the last factor of the decay path fused in (paper: Method, "Finch-C2
+ * Time Mixing": lora(x) = lambda + tanh(x A) B and d_t = lora_omega(ddlerp_d(x_t, x_{t-1})),
+ * w_t = exp(-exp(d_t))).  Instead of the decay logits x [B][T][H][N] the call takes the low-rank
+ * activations and the outer factor and forms the logits on the matrix cores, in fp32, chunk by
+ * chunk, so they never exist in HBM:
+ *
+ *     d[b][t][h][n] = lambda[h*N + n] + sum_{k<R} y[b][t][k] * b_omega[k][h*N + n]
+ *
+ *   y        [B][T][R]   bf16  tanh(ddlerp_d(x_t, x_{t-1}) A_omega), shared by all heads; R must
+ *                              be 64 (WKV6_ERR_UNSUPPORTED otherwise)
+ *   lambda   [H*N]       fp32
+ *   b_omega  [R][H*N]    bf16
+ * all device pointers, 16-byte aligned.  The per-token-head input traffic drops from five bf16
+ * rows to four (y is 128 bytes per token for all heads together).  `moments` may be NULL; if
+ * not, the per-head LayerNorm partials are written as by wkv6_finch_c2_prefill_bf16_moments.
+ * Everything else (kbar, uprime, layouts, state, T and B edge cases, value range, errors) is as
+ * for wkv6_finch_c2_prefill_bf16; always the chunked kernel.
+ */
+int wkv6_finch_c2_prefill_lora_bf16(int B, int T, int H, int N, int R,
+                                    const void *r, const void *kbar, const void *v,
+                                    const void *y, const float *lambda, const void *b_omega,
+                                    const void *uprime, const float *state_in,
+                                    void *out, float *moments, float *state_out, void *stream);
+
+/*
  * Serving shapes: the same recurrence for one token (decode) or a few tokens (append) per
  * sequence and many sequences, where the cost is streaming each fp32 state through once
  * (paper: GoldFinch pre-fill is an RNN pass, so a cache is extended token by token with the

@@ -53,6 +53,7 @@ int run(int B, int T, int H, int N, const void* r, const void* k, const void* v,
     a.batch_stride = batch_stride;
     a.segs = 1; a.T_last = T; a.seg_stride = 0; a.decay_out = nullptr; a.unit_stride = 0;
     a.moments = moments;
+    a.y = nullptr; a.lambda = nullptr; a.bw = nullptr;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;
@@ -125,6 +126,39 @@ int wkv6_finch_c2_prefill_bf16_moments(int B, int T, int H, int N, const void* r
     return run(B, T, H, N, r, kbar, v, x, nullptr, state_in, out, state_out,
                static_cast<long long>(T) * H * N, true, false, Path::kChunked, stream, uprime, true, moments,
                true);
+}
+
+int wkv6_finch_c2_prefill_lora_bf16(int B, int T, int H, int N, int R, const void* r, const void* kbar,
+                                    const void* v, const void* y, const float* lambda, const void* b_omega,
+                                    const void* uprime, const float* state_in, void* out, float* moments,
+                                    float* state_out, void* stream) {
+    if (N != wkv6::kHeadSize || R != wkv6::kLoraRank) return WKV6_ERR_UNSUPPORTED;
+    if (B < 0 || T < 0 || H < 1 || H > 262144) return WKV6_ERR_SHAPE;
+    if (B == 0) return WKV6_OK;
+    if (T > 0) {
+        if (!r || !kbar || !v || !y || !lambda || !b_omega || !uprime || !out) return WKV6_ERR_NULL;
+        if (misaligned(r) || misaligned(kbar) || misaligned(v) || misaligned(y) || misaligned(lambda) ||
+            misaligned(b_omega) || misaligned(uprime) || misaligned(out) || misaligned(moments))
+            return WKV6_ERR_ALIGN;
+    }
+    if (misaligned(state_in) || misaligned(state_out)) return WKV6_ERR_ALIGN;
+    if (static_cast<long long>(B) * H > 0x7fffffffLL) return WKV6_ERR_SHAPE;
+
+    wkv6::Args a;
+    a.B = B; a.T = T; a.H = H;
+    a.r = r; a.k = kbar; a.v = v; a.x = nullptr; a.u = nullptr;
+    a.finch_c2 = true;
+    a.uprime = uprime;
+    a.state_in = state_in; a.out = out; a.state_out = state_out;
+    a.batch_stride = static_cast<long long>(T) * H * N;
+    a.segs = 1; a.T_last = T; a.seg_stride = 0; a.decay_out = nullptr; a.unit_stride = 0;
+    a.moments = moments;
+    a.y = y; a.lambda = lambda; a.bw = b_omega;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipError_t err = T == 0 ? wkv6::launch_state_passthrough(a, s)
+                                  : wkv6::launch_chunked(a, moments ? wkv6::ChunkedMode::kBf16OutLoraMoments
+                                                                    : wkv6::ChunkedMode::kBf16OutLora, s);
+    return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
 }
 
 int wkv6_layernorm_finalize(int B, int T, int H, int N, const float* moments, float eps, float* mean_rstd,
@@ -208,7 +242,7 @@ const char* wkv6_status_string(int status) {
     }
 }
 
-int wkv6_version(void) { return 410; }
+int wkv6_version(void) { return 420; }
 
 }  // extern "C"
 
@@ -292,6 +326,7 @@ int run_split(int B, int T, int H, int N, const void* r, const void* k, const vo
     a.uprime = finch_c2 ? uprime : nullptr;
     a.batch_stride = static_cast<long long>(T) * H * N;
     a.segs = p.segs; a.T_last = p.last_len; a.unit_stride = 0; a.moments = nullptr;
+    a.y = nullptr; a.lambda = nullptr; a.bw = nullptr;
     a.seg_stride = static_cast<long long>(p.seg_len) * H * N;
     // pass 1: every segment from a zero state, no output: its local state and total decay
     a.state_in = nullptr; a.out = nullptr; a.state_out = seg_state; a.decay_out = seg_decay;

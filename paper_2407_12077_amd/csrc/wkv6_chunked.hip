@@ -56,6 +56,7 @@ typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kChunk = 32;                 // tokens per chunk
 constexpr int kProducerGroups = 3;         // 4 waves each
@@ -85,6 +86,16 @@ enum : int {
     kLdsBytes = 2 * kBuf
 };
 static_assert(kBuf % 16 == 0 && kLdsBytes <= 160 * 1024, "LDS budget");
+
+// Fused decay path only: the chunk's decay logits d[channel pair][parity][token] in fp32, written
+// by the consumers and read by the producers' phase D, one buffer per chunk parity after the
+// two main buffers.  272 bytes per channel pair (2 x 32 tokens x 4 + 16 pad): the 16-byte
+// accesses of 16 neighbouring lanes, a channel pair apart, cover all banks once.
+constexpr int kDxPair = 2 * kChunk * 4 + 16;
+constexpr int kDxBuf = 32 * kDxPair;
+constexpr int kDx = kLdsBytes;
+constexpr int kLdsBytesLora = kLdsBytes + 2 * kDxBuf;
+static_assert(kLdsBytesLora <= 160 * 1024, "LDS budget");
 
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -178,13 +189,18 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const char* base, l
 
 // A chunk's loads are issued in two halves (x and r; k and v) so that two different phases can
 // share the cost of issuing them.
-template <bool kSkipR>
+template <bool kSkipR, bool kSkipX>
 __device__ __forceinline__ void load_rows_xr(Raw& d, const Streams& st, long long unit_bytes, int t0,
                                              const int (&voff)[4]) {
     const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
-    const __amdgpu_buffer_rsrc_t rx = chunk_rsrc(st.x + unit_bytes, off, st.span_bytes);
+    if constexpr (!kSkipX) {
+        const __amdgpu_buffer_rsrc_t rx = chunk_rsrc(st.x + unit_bytes, off, st.span_bytes);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, kStreamOnce);
+        for (int s = 0; s < 4; ++s) d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, kStreamOnce);
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) d.x[s] = 0u;
+    }
     if constexpr (!kSkipR) {
         const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r + unit_bytes, off, st.span_bytes);
 #pragma unroll
@@ -275,7 +291,8 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                                          const Units& un, long long tok_stride, int T) {
     constexpr bool kOutF32 = kMode == 1;
     constexpr bool kStateOnly = kMode == 2;
-    constexpr bool kMoments = kMode == 3;        // bf16 out plus the per-head LayerNorm partials
+    constexpr bool kMoments = kMode == 3 || kMode == 5;   // bf16 out plus the per-head LayerNorm partials
+    constexpr bool kLora = kMode >= 4;           // decay logits from the consumers (LDS), not from x
     constexpr bool kStageF32 = kOutF32 || kC2;   // staging precision of the finished rows
     const int lane = tid & 63;
     const int gtid = tid & 255;              // thread inside the group
@@ -331,10 +348,25 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                 if (t0 + 4 * g8 + s >= T) cur.x[s] = 0xff80ff80u;      // bf16 -inf, twice
         }
         float w[2][4];
+        if constexpr (kLora) {
+            // the chunk's logits were left in LDS by the consumers one window ago: this thread's
+            // 4 tokens of its two channels
+            const char* dx = lds_all + kDx + (g & 1) * kDxBuf + cp * kDxPair + g8 * 16;
+            const float4 de = *reinterpret_cast<const float4*>(dx);
+            const float4 dq = *reinterpret_cast<const float4*>(dx + kChunk * 4);
+            const float d0[4] = {de.x, de.y, de.z, de.w}, d1[4] = {dq.x, dq.y, dq.z, dq.w};
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            w[0][s] = decay_of(bf16_lo(cur.x[s]));
-            w[1][s] = decay_of(bf16_hi(cur.x[s]));
+            for (int s = 0; s < 4; ++s) {
+                const bool past = t0 + 4 * g8 + s >= T;          // tokens past the end: w = 1
+                w[0][s] = past ? 1.f : decay_of(d0[s]);
+                w[1][s] = past ? 1.f : decay_of(d1[s]);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                w[0][s] = decay_of(bf16_lo(cur.x[s]));
+                w[1][s] = decay_of(bf16_hi(cur.x[s]));
+            }
         }
         // products of decays inside the group, fp32: prefix of token 2 and 3, suffix of token 1
         // and 0, and the group total
@@ -600,7 +632,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     stc.advance(0, un.nchunks);
     auto fetch_xr = [&](Raw& buf, const Cursor<kMulti>& at) {
         const bool live = at.live(un);                // uniform; dead: offset past the span = empty descriptor
-        load_rows_xr<kStateOnly>(buf, st, live ? at.unit_elems(un) * 2 : 0, live ? at.c * kChunk : T + kChunk, voff);
+        load_rows_xr<kStateOnly, kLora>(buf, st, live ? at.unit_elems(un) * 2 : 0, live ? at.c * kChunk : T + kChunk, voff);
     };
     auto fetch_kv = [&](Raw& buf, const Cursor<kMulti>& at) {
         const bool live = at.live(un);
@@ -660,6 +692,7 @@ template <int kMode, bool kC2, bool kMulti>
 __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane, int cw, const Units& un) {
     constexpr bool kOutF32 = kMode == 1;
     constexpr bool kStateOnly = kMode == 2;
+    constexpr bool kLora = kMode >= 4;
     const int l16 = lane & 15;
     const int g4 = lane >> 4;
     const int j = 16 * cw + l16;            // value column of this lane
@@ -690,12 +723,72 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
     // 4-channel granule (l16&3) of a 16-channel block
     const int tr_lane = (8 * g4 + (l16 >> 2)) * kRow + 8 * (l16 & 3);
 
-    __syncthreads();                                                            // start barrier
     const int total = un.count * un.nchunks;
     const int nwin = (total + 6) / 3 * 3;
+
+    // Fused decay path.  This wave forms the decay logits of its 16 channels (16cw .. 16cw+15, as
+    // key channels) for all 32 tokens of the chunk the producers digest in the next window:
+    // d = lambda + y B_h, two 16-token row blocks x two 32-wide steps over the rank, bf16 operands
+    // (exact products) with fp32 accumulation started at lambda.  The head's 64x16 slice of B
+    // stays in registers for the whole kernel; y rows (128 bytes per token, shared by all heads,
+    // so served by L2) are requested at the start of a window and used at its end.
+    [[maybe_unused]] bf16x8 bw[2];
+    [[maybe_unused]] bf16x8 ya[2][2];
+    [[maybe_unused]] float lam = 0.f;
+    [[maybe_unused]] int y_b0 = 0, y_bstep = 0;
+    [[maybe_unused]] const int y_voff = l16 * (kLoraRank * 2) + 16 * g4;
+    if constexpr (kLora) {
+        const int width = a.H * kHeadSize;
+        const int col = (un.first % a.H) * kHeadSize + 16 * cw + l16;
+        const unsigned short* bwp = static_cast<const unsigned short*>(a.bw);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                bw[ks][e] = __builtin_bit_cast(__bf16, bwp[static_cast<long long>(32 * ks + 8 * g4 + e) * width + col]);
+        lam = a.lambda[col];
+        y_b0 = un.first / a.H;
+        y_bstep = un.stride / a.H;
+    }
+    auto y_fetch = [&](const Cursor<kMulti>& dn) {
+        const long long batch = y_b0 + (kMulti ? static_cast<long long>(dn.ui) * y_bstep : 0);
+        const long long seq_bytes = static_cast<long long>(a.T) * (kLoraRank * 2);
+        const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(static_cast<const char*>(a.y) + batch * seq_bytes,
+                                                     static_cast<long long>(dn.c) * kChunk * (kLoraRank * 2), seq_bytes);
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                ya[rt][ks] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+                                                            ry, y_voff + 16 * rt * (kLoraRank * 2) + 64 * ks, 0, 0));
+    };
+    auto d_finish = [&](int pos) {                   // pos: the chunk's position in the sequence (LDS parity)
+        char* dx = lds_all + kDx + (pos & 1) * kDxBuf + (8 * cw + (l16 >> 1)) * kDxPair + (l16 & 1) * (kChunk * 4) + 16 * g4;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            float4v acc = {lam, lam, lam, lam};
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ya[rt][0], bw[0], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ya[rt][1], bw[1], acc, 0, 0, 0);
+            *reinterpret_cast<float4v*>(dx + 64 * rt) = acc;     // tokens 16rt + 4g4 .. +3 of this lane's channel
+        }
+    };
+    Cursor<kMulti> dn{0, 0};                         // the chunk whose logits are formed next
+    if constexpr (kLora) {
+        if (total > 0) {
+            y_fetch(dn);
+            d_finish(0);
+            dn.advance(1, un.nchunks);
+        }
+    }
+
+    __syncthreads();                                                            // start barrier
     Cursor<kMulti> at{0, 0};                         // chunk n-2 of the sequence: the state chain's
 #pragma clang loop unroll(disable)
     for (int n = 0; n < nwin; ++n) {
+        [[maybe_unused]] const bool dlive = kLora && n + 1 < total;
+        if constexpr (kLora) {
+            if (dlive) y_fetch(dn);
+        }
         if (!kStateOnly && n >= 3 && n - 3 < total) {
             // chunk n-3: o += A V (two partial score tiles), then stage for the producers' stores
             char* lds = lds_all + ((n - 3) & 1) * kBuf;
@@ -771,6 +864,12 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
                 if (a.decay_out && cw == 0) a.decay_out[unit * kHeadSize + lane] = dtot;
             }
             at.advance(1, un.nchunks);
+        }
+        if constexpr (kLora) {
+            if (dlive) {
+                d_finish(n + 1);
+                dn.advance(1, un.nchunks);
+            }
         }
         __syncthreads();                                                        // window barrier
     }
@@ -869,11 +968,12 @@ hipError_t launch_mode(const Args& args, hipStream_t stream) {
         }
     }
     const dim3 grid(static_cast<unsigned>(units));
+    constexpr int lds_bytes = kMode >= 4 ? kLdsBytesLora : kLdsBytes;
     auto go = [&](auto kernel) {
         const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), kLdsBytes, stream, a);
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, stream, a);
         return hipGetLastError();
     };
     if constexpr (kMode != 2) {
@@ -890,9 +990,14 @@ hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream) {
         case ChunkedMode::kBf16Out: return c2 ? launch_mode<0, true>(a, stream) : launch_mode<0, false>(a, stream);
         case ChunkedMode::kF32Out: return c2 ? launch_mode<1, true>(a, stream) : launch_mode<1, false>(a, stream);
         case ChunkedMode::kStateOnly: return c2 ? launch_mode<2, true>(a, stream) : launch_mode<2, false>(a, stream);
-        default:
+        case ChunkedMode::kBf16OutMoments:
             if (!c2 || a.segs != 1 || !a.moments) return hipErrorInvalidValue;
             return launch_mode<3, true>(a, stream);
+        default:
+            if (!c2 || a.segs != 1 || !a.y || !a.lambda || !a.bw) return hipErrorInvalidValue;
+            if (mode == ChunkedMode::kBf16OutLora) return launch_mode<4, true>(a, stream);
+            if (!a.moments) return hipErrorInvalidValue;
+            return launch_mode<5, true>(a, stream);
     }
 }
 

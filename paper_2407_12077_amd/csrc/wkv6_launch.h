@@ -32,11 +32,18 @@ struct Args {
     float* moments;           // kBf16OutMoments only: [B][H][T][2] per (batch, head, token): the sum of
                               // the head's N output values and their squared deviations from the
                               // head's own mean (taken before the rounding to bf16)
+    // kBf16OutLora / kBf16OutLoraMoments only (x unused): the decay logit is formed in the kernel as
+    // d[b][t][h][n] = lambda[h*N+n] + sum_k y[b][t][k] * bw[k][h*N+n], k < 64
+    const void* y;            // [B][T][64] bf16
+    const float* lambda;      // [H*N] fp32
+    const void* bw;           // [64][H*N] bf16
     int unit_stride;          // set by launch_chunked: 0 = one unit per workgroup; otherwise workgroup w
                               // handles units w, w + unit_stride, ... (a multiple of H, segs == 1 only)
 };
 
-enum class ChunkedMode { kBf16Out, kF32Out, kStateOnly, kBf16OutMoments };
+enum class ChunkedMode { kBf16Out, kF32Out, kStateOnly, kBf16OutMoments, kBf16OutLora, kBf16OutLoraMoments };
+
+constexpr int kLoraRank = 64;   // R: the only rank of the decay path the fused kernel is built for
 
 // Token-by-token fp32 kernel; inputs bf16 or fp32 (fp32 inputs: fp32 out, Finch form only);
 // with bf16 inputs the output is fp32 or bf16 and a.finch_c2 selects the form.
@@ -44,7 +51,8 @@ hipError_t launch_recurrent(const Args& a, bool in_bf16, bool out_bf16, hipStrea
 
 // Chunked matrix-core kernel; inputs bf16, out bf16 or fp32, or (kStateOnly) no output at all:
 // only state_out and decay_out of every unit, from r-independent work.  kBf16OutMoments: bf16 out
-// plus a.moments, Finch-C2 form and segs == 1 only.
+// plus a.moments, Finch-C2 form and segs == 1 only.  kBf16OutLora(Moments): the same with the
+// decay logits formed in the kernel from a.y, a.lambda, a.bw instead of read from a.x.
 hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream);
 
 // Token-split support: folds the per-segment (decay, local state) pairs of every (batch, head)

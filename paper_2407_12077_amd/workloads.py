@@ -132,6 +132,22 @@ def make_uprime(cfg, seed=None):
     return round_to_bf16(a) if cfg.dtype == "bf16" else a
 
 
+def make_decay_lora_inputs(cfg, seed=None, rank=64):
+    """Inputs of the fused decay path for ``cfg``: low-rank activations y [B, T, rank] (tanh of
+    N(0,1) draws, so inside (-1, 1) like the tanh(. A) they stand in for), per-channel base logits
+    lam [H*N] ~ U(-5.5, 0.5) and the outer factor b_omega [rank, H*N] ~ N(0, 0.2^2), which puts the
+    token-dependent part of the logit at a standard deviation of about 1 around its base (the
+    logits then span roughly the U(-6, 1) range of the plain workloads).  y and b_omega are rounded
+    to bf16; all are float32 arrays.  Own generator, ``PCG64(seed + 2000)``."""
+    if seed is None:
+        seed = BASE_SEED + cfg.index
+    rng = np.random.Generator(np.random.PCG64(seed + 2000))
+    y = np.tanh(rng.standard_normal((cfg.B, cfg.T, rank), dtype=np.float32))
+    lam = (rng.random(cfg.H * cfg.N, dtype=np.float32) * np.float32(6.0) - np.float32(5.5)).astype(np.float32)
+    b_omega = rng.standard_normal((rank, cfg.H * cfg.N), dtype=np.float32) * np.float32(0.2)
+    return {"y": round_to_bf16(y), "lam": lam, "b_omega": round_to_bf16(b_omega)}
+
+
 def make_key_compress_inputs(M, D, seed=BASE_SEED + 100):
     """Inputs of the GOLD key compression for M tokens of a model of width D: hidden states
     x [M, D] ~ N(0, 1) (a residual-stream activation stands in for the last Finch-C2 layer's

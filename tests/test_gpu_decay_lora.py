@@ -1,0 +1,158 @@
+"""GPU parity of the Finch-C2 prefill with the last factor of the decay path fused in (Method
+section, Finch-C2 Time Mixing: lora(x) = lambda + tanh(x A) B, d_t = lora_omega(...),
+w_t = exp(-exp(d_t))) against the fp64 oracles, through the C ABI.
+
+Oracle chain: d = decay_logits_numpy(y, lambda, B) in fp64, then the Finch-C2 time-mix oracle on
+(r, kbar, v, d, u').  The C oracle takes float arrays, so d is rounded to float32 on the way
+(relative 6e-8: far below the bar)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_12077_amd as wkv
+from oracle import decay_logits_numpy, finch_c2_oracle, head_moments_numpy
+from paper_2407_12077_amd.workloads import (CONFIGS, make_decay_lora_inputs, make_inputs, make_uprime, round_to_bf16,
+                                            scaled)
+
+from gpu_util import BF16_OUT_ROUNDING, TOL_BF16, max_norm_err, to_dev
+
+pytestmark = pytest.mark.gpu
+R = 64
+
+
+def inputs(cfg, seed=None):
+    inp = make_inputs(cfg, seed)
+    inp["uprime"] = make_uprime(cfg, seed)
+    inp.update(make_decay_lora_inputs(cfg, seed, R))
+    return inp
+
+
+def run_lora(inp, want_moments=False):
+    B, T, H, N = inp["r"].shape
+    r, k, v, up, y, bo = (to_dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "uprime", "y", "b_omega"))
+    lam = to_dev(inp["lam"], torch.float32)
+    s_in = to_dev(inp.get("state_in"), torch.float32)
+    out = torch.full((B, T, H, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    s_out = torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda")
+    mom = torch.full((B, H, T, 2), float("nan"), dtype=torch.float32, device="cuda") if want_moments else None
+    wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, R, r, k, v, y, lam, bo, up, s_in, out, mom, s_out)
+    torch.cuda.synchronize()
+    f64 = lambda t: None if t is None else t.float().cpu().numpy().astype(np.float64)
+    return f64(out), f64(s_out), f64(mom)
+
+
+def oracle(inp):
+    B, T, H, N = inp["r"].shape
+    d = decay_logits_numpy(inp["y"], inp["lam"], inp["b_omega"], H, N)
+    return finch_c2_oracle(inp["r"], inp["k"], inp["v"], d.astype(np.float32), inp["uprime"], inp.get("state_in"))
+
+
+def check(inp):
+    o_ref, s_ref = oracle(inp)
+    o, s, _ = run_lora(inp)
+    eo, es = max_norm_err(o, o_ref), max_norm_err(s, s_ref)
+    assert eo <= TOL_BF16 + BF16_OUT_ROUNDING and es <= TOL_BF16, (eo, es)
+    return eo, es
+
+
+@pytest.mark.parametrize("T", [1, 2, 7, 31, 32, 33, 63, 64, 65, 96, 97, 129, 200, 1000])
+def test_lengths(gpu_device, T):
+    check(inputs(scaled(CONFIGS[2], B=2, T=T, H=3)))
+
+
+@pytest.mark.parametrize("cfg_index", [2, 4, 5])
+def test_reduced_configs(gpu_device, cfg_index):
+    dims = {2: dict(B=2, T=700, H=4), 4: dict(B=5, T=512, H=3), 5: dict(B=1, T=1500, H=6)}[cfg_index]
+    eo, es = check(inputs(scaled(CONFIGS[cfg_index], **dims)))
+    print(f"fused decay path, reduced config {cfg_index}: err_out={eo:.3e} err_state={es:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("B,T,H", [(70, 45, 4), (300, 20, 3), (5, 40, 96), (2, 33, 260)])
+def test_many_units_per_workgroup(gpu_device, B, T, H):
+    check(inputs(scaled(CONFIGS[4], B=B, T=T, H=H)))
+
+
+def test_zero_activations_give_the_base_logits(gpu_device):
+    """y = 0: the logits are lambda for every token; the plain entry fed x = lambda (a bf16-exact
+    lambda) runs the same arithmetic from there on, so the results agree bit for bit."""
+    cfg = scaled(CONFIGS[2], B=2, T=100, H=3)
+    inp = inputs(cfg)
+    inp["y"][:] = 0.0
+    inp["lam"] = round_to_bf16(inp["lam"])
+    o, s, _ = run_lora(inp)
+    B, T, H, N = inp["r"].shape
+    x = np.broadcast_to(inp["lam"].reshape(1, 1, H, N), (B, T, H, N))
+    r, k, v, up, xd = (to_dev(a, torch.bfloat16) for a in (inp["r"], inp["k"], inp["v"], inp["uprime"], x))
+    out = torch.empty((B, T, H, N), dtype=torch.bfloat16, device="cuda")
+    s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
+    wkv.wkv6_finch_c2_prefill_bf16(B, T, H, N, r, k, v, xd, up, None, out, s_out)
+    torch.cuda.synchronize()
+    assert np.array_equal(o, out.float().cpu().numpy()) and np.array_equal(s, s_out.cpu().numpy())
+    check(inp)
+
+
+def test_extreme_logits(gpu_device):
+    """Base logits from -40 (w = 1 to the last bit) to +6 (w = 0): no clamp on either side."""
+    inp = inputs(scaled(CONFIGS[2], B=1, T=150, H=2))
+    inp["lam"] = np.tile(np.linspace(-40.0, 6.0, 64, dtype=np.float32), 2)
+    check(inp)
+
+
+def test_with_moments(gpu_device):
+    inp = inputs(scaled(CONFIGS[4], B=3, T=77, H=4))
+    o_ref, s_ref = oracle(inp)
+    o, s, mom = run_lora(inp, want_moments=True)
+    o2, s2, _ = run_lora(inp)
+    assert np.array_equal(o, o2) and np.array_equal(s, s2)
+    sum_ref, m2_ref = head_moments_numpy(o_ref)
+    delta = TOL_BF16 * np.abs(o_ref).max()
+    assert np.abs(mom[..., 0] - sum_ref).max() <= 64 * delta
+    assert (np.abs(mom[..., 1] - m2_ref) <= 4 * delta * np.sqrt(64 * m2_ref) + 4 * 64 * delta ** 2).all()
+
+
+def test_full_size_config2_sampled_units(gpu_device):
+    """The benchmark's launch configuration at full size; the oracle recomputes a seeded sample
+    of (batch, head) units in full."""
+    cfg = CONFIGS[2]
+    inp = inputs(cfg)
+    B, T, H, N = inp["r"].shape
+    r, k, v, up, y, bo = (to_dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "uprime", "y", "b_omega"))
+    lam = to_dev(inp["lam"], torch.float32)
+    out = torch.empty((B, T, H, N), dtype=torch.bfloat16, device="cuda")
+    s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
+    wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, R, r, k, v, y, lam, bo, up, None, out, None, s_out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(s_out).all()
+    rng = np.random.default_rng(2004)
+    units = {(0, 0), (B - 1, H - 1)}
+    while len(units) < 8:
+        units.add((int(rng.integers(B)), int(rng.integers(H))))
+    worst_o = worst_s = 0.0
+    for (b, h) in sorted(units):
+        sl = lambda a: np.ascontiguousarray(a[b:b + 1, :, h:h + 1])
+        d = decay_logits_numpy(inp["y"][b:b + 1], inp["lam"][h * N:(h + 1) * N], inp["b_omega"][:, h * N:(h + 1) * N], 1, N)
+        o_ref, s_ref = finch_c2_oracle(sl(inp["r"]), sl(inp["k"]), sl(inp["v"]), d.astype(np.float32), sl(inp["uprime"]),
+                                       None, nthreads=1)
+        worst_o = max(worst_o, max_norm_err(out[b, :, h].float().cpu().numpy(), o_ref[0, :, 0]))
+        worst_s = max(worst_s, max_norm_err(s_out[b, h].cpu().numpy(), s_ref[0, 0]))
+    print(f"fused decay path, config 2: {len(units)} units, worst err_out={worst_o:.3e} err_state={worst_s:.3e}", flush=True)
+    assert worst_o <= TOL_BF16 + BF16_OUT_ROUNDING and worst_s <= TOL_BF16
+
+
+def test_validation(gpu_device):
+    B, T, H, N = 1, 8, 2, 64
+    z = torch.zeros((B, T, H, N), dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros((B, T, R), dtype=torch.bfloat16, device="cuda")
+    lam = torch.zeros(H * N, dtype=torch.float32, device="cuda")
+    bo = torch.zeros((R, H * N), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty_like(z)
+    with pytest.raises(wkv.Wkv6Error):                         # rank
+        wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, 32, z, z, z, y, lam, bo, z, None, out, None, None)
+    with pytest.raises(wkv.Wkv6Error):                         # missing outer factor
+        wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, R, z, z, z, y, lam, None, z, None, out, None, None)
+    with pytest.raises(wkv.Wkv6Error):                         # misaligned activations
+        wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, R, z, z, z, y.view(-1)[4:], lam, bo, z, None, out, None, None)
+    wkv.wkv6_finch_c2_prefill_lora_bf16(B, 0, H, N, R, None, None, None, None, None, None, None, None, None, None, None)
+    wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, R, z, z, z, y, lam, bo, z, None, out, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(out, torch.zeros_like(out))
