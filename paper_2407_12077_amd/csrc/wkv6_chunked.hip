@@ -701,20 +701,33 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
 
     // S[nb][e] = state[n = 16nb + 4g4 + e][j]; Snext: the state entering the workgroup's next
     // unit, fetched while the current unit is still being processed
-    float4v S[4], Snext[4];
+    // State traffic goes through a raw buffer descriptor of the unit's 16 KiB with the
+    // (nb, e) part of the offset as a scalar: one vector register of addressing for all 16
+    // accesses instead of a 64-bit address each.
+    float4v S[4];
+    [[maybe_unused]] float4v Snext[4];
+    const int state_voff = (4 * g4 * 64 + j) * 4;
+    auto state_rsrc = [&](const float* base, int ui) {
+        const long long unit = static_cast<long long>(un.first) + static_cast<long long>(ui) * un.stride;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base + unit * 4096), 0, 4096 * 4, 0x00020000);
+    };
     auto fetch_state = [&](float4v (&dst)[4], int ui) {
         if (a.state_in && ui < un.count) {
-            const float* s0 = a.state_in + (static_cast<long long>(un.first) + static_cast<long long>(ui) * un.stride) * 4096;
+            const __amdgpu_buffer_rsrc_t rs = state_rsrc(a.state_in, ui);
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) dst[nb][e] = s0[(16 * nb + 4 * g4 + e) * 64 + j];
+                for (int e = 0; e < 4; ++e)
+                    dst[nb][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, state_voff, (16 * nb + e) * 256, 0));
         } else {
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) dst[nb] = float4v{0.f, 0.f, 0.f, 0.f};
         }
     };
-    fetch_state(Snext, 0);
+    if constexpr (kMulti)
+        fetch_state(Snext, 0);
+    else
+        fetch_state(S, 0);
 
     float dtot = 1.f;   // product of all decays so far, key channel `lane` (only with decay_out)
     float4v o[2];       // output rows of the chunk whose state chain ran last: 2 t-blocks x 4 rows
@@ -814,9 +827,11 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
             const char* lds = lds_all + (n & 1) * kBuf;
             if (at.c == 0) {
                 // a unit begins: take its entering state, start fetching the next unit's
+                if constexpr (kMulti) {
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb) S[nb] = Snext[nb];
-                fetch_state(Snext, at.ui + 1);
+                    for (int nb = 0; nb < 4; ++nb) S[nb] = Snext[nb];
+                    fetch_state(Snext, at.ui + 1);
+                }
                 dtot = 1.f;
             }
             // inter-chunk read: o[t][j] = sum_n (r_t W(t,-1))[n] S[n][j]; the state registers,
@@ -855,11 +870,15 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
                 // the unit ends: its final state and, if asked for, its total decay
                 const long long unit = static_cast<long long>(un.first) + static_cast<long long>(at.ui) * un.stride;
                 if (a.state_out) {
-                    float* so = a.state_out + unit * 4096;
+                    const __amdgpu_buffer_rsrc_t rs = state_rsrc(a.state_out, at.ui);
 #pragma unroll
                     for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) so[(16 * nb + 4 * g4 + e) * 64 + j] = S[nb][e];
+                        for (int e = 0; e < 4; ++e) {
+                            const float value = S[nb][e];        // (a bit cast straight from the vector element reads element 0)
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value), rs, state_voff,
+                                                                  (16 * nb + e) * 256, 0);
+                        }
                 }
                 if (a.decay_out && cw == 0) a.decay_out[unit * kHeadSize + lane] = dtot;
             }
@@ -884,7 +903,14 @@ __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
     __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), 1);
     const int tid = threadIdx.x;
     const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int unit = blockIdx.x;                 // (batch * segs + segment) * H + head
+    int unit = blockIdx.x;                       // (batch * segs + segment) * H + head
+    if constexpr (kMode >= 4) {
+        // Fused decay path: the heads of a batch share its y rows.  Workgroups go to the 8 XCDs
+        // (each with its own L2) round-robin by index, so give XCD i the i-th eighth of the
+        // units: neighbouring heads of a batch then read y through the same L2.
+        const int per_xcd = gridDim.x >> 3;
+        if ((gridDim.x & 7) == 0) unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    }
     const int bs = unit / a.H;
     const int h = unit - bs * a.H;
     const int b = bs / a.segs;
