@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2407_12077_amd as wkv
@@ -137,3 +138,46 @@ def test_split_helpers_and_validation():
     assert f(1, 4096, 2, 64, A, A, A, A, A, None, A, A, 9, 4, A, 1 << 30, None) == 3      # dtype code
     assert f(1, 4096, 2, 64, A, A, A, A, A, None, A, A, 1, 0, A, 1 << 30, None) == 2      # segments < 1
     assert f(1, 4096, 2, 32, A, A, A, A, A, None, A, A, 1, 4, A, 1 << 30, None) == 3      # N != 64
+
+
+def test_layernorm_moments_validation():
+    f = _raw("wkv6_finch_c2_prefill_bf16_moments")
+    assert f(1, 8, 2, 64, A, A, A, A, A, None, A, None, A, None) == 1          # moments required when T > 0
+    assert f(1, 8, 2, 64, A, A, A, A, A, None, A, P(0x1004), A, None) == 5
+    assert f(1, 8, 2, 32, A, A, A, A, A, None, A, A, A, None) == 3
+    assert f(0, 8, 2, 64, None, None, None, None, None, None, None, None, None, None) == 0
+    g = _raw("wkv6_layernorm_finalize")
+    assert g(1, 8, 2, 32, A, ctypes.c_float(1e-5), A, None) == 3
+    assert g(1, 8, 0, 64, A, ctypes.c_float(1e-5), A, None) == 2
+    assert g(70000, 8, 2, 64, A, ctypes.c_float(1e-5), A, None) == 2             # grid limit
+    assert g(1, 8, 2, 64, A, ctypes.c_float(-1.0), A, None) == 2
+    assert g(1, 8, 2, 64, A, ctypes.c_float(float("nan")), A, None) == 2
+    assert g(1, 8, 2, 64, None, ctypes.c_float(1e-5), A, None) == 1
+    assert g(1, 8, 2, 64, A, ctypes.c_float(1e-5), P(0x1008), None) == 5
+    assert g(1, 0, 2, 64, None, ctypes.c_float(1e-5), None, None) == 0
+
+
+def test_fused_decay_path_validation():
+    f = _raw("wkv6_finch_c2_prefill_lora_bf16")
+    ok = (A, A, A, A, A, A, A, None, A, None, A, None)    # r kbar v y lambda b_omega uprime state_in out moments state_out stream
+    assert f(1, 8, 2, 64, 32, *ok) == 3                                          # rank
+    assert f(1, 8, 2, 32, 64, *ok) == 3                                          # head size
+    assert f(1, -8, 2, 64, 64, *ok) == 2
+    assert f(1, 8, 2, 64, 64, A, A, A, None, A, A, A, None, A, None, A, None) == 1   # y
+    assert f(1, 8, 2, 64, 64, A, A, A, A, None, A, A, None, A, None, A, None) == 1   # lambda
+    assert f(1, 8, 2, 64, 64, A, A, A, A, A, None, A, None, A, None, A, None) == 1   # b_omega
+    assert f(1, 8, 2, 64, 64, A, A, A, P(0x1008), A, A, A, None, A, None, A, None) == 5
+    assert f(1, 8, 2, 64, 64, A, A, A, A, A, A, A, None, A, P(0x1004), A, None) == 5   # moments alignment
+    assert f(0, 8, 2, 64, 64, *([None] * 12)) == 0
+
+
+def test_decay_lora_workload_recipe():
+    from paper_2407_12077_amd.workloads import CONFIGS, make_decay_lora_inputs, round_to_bf16, scaled
+    cfg = scaled(CONFIGS[2], B=2, T=50, H=3)
+    a, b = make_decay_lora_inputs(cfg), make_decay_lora_inputs(cfg)
+    assert a["y"].shape == (2, 50, 64) and a["lam"].shape == (3 * 64,) and a["b_omega"].shape == (64, 3 * 64)
+    for k in a:
+        assert a[k].dtype == np.float32 and np.array_equal(a[k], b[k])            # seeded
+    assert np.array_equal(a["y"], round_to_bf16(a["y"])) and np.array_equal(a["b_omega"], round_to_bf16(a["b_omega"]))
+    assert np.abs(a["y"]).max() <= 1.0 and -5.5 <= a["lam"].min() and a["lam"].max() <= 0.5
+    assert not np.array_equal(a["y"], make_decay_lora_inputs(cfg, seed=1)["y"])
