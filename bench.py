@@ -139,7 +139,7 @@ def main():
                     choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent",
                              "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
                              "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_moments",
-                             "wkv6_finch_c2_prefill_lora_bf16", "wkv6_decode_bf16", "wkv6_key_compress_bf16"])
+                             "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16", "wkv6_decode_bf16", "wkv6_key_compress_bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 512 MiB device copy (calibrates rocprofv3 byte counters)")
@@ -179,7 +179,7 @@ def main():
         up = dev(inp["uprime"], torch.bfloat16)
     out_f32 = args.entry not in ("wkv6_prefill_bf16", "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
                                  "wkv6_finch_c2_prefill_bf16_moments", "wkv6_finch_c2_prefill_lora_bf16",
-                                 "wkv6_decode_bf16")
+                                 "wkv6_prefill_lora_bf16", "wkv6_decode_bf16")
     out = torch.empty((B, T, H, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device="cuda")
     s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
     fn = getattr(wkv, args.entry)
@@ -209,7 +209,7 @@ def main():
         def step():                              # the prefill with its LayerNorm partials, then their fold
             fn(B, T, H, N, r, k, v, x, up, s_in, out, moments, s_out, stream.cuda_stream)
             wkv.wkv6_layernorm_finalize(B, T, H, N, moments, 1e-5, mean_rstd, stream.cuda_stream)
-    elif args.entry == "wkv6_finch_c2_prefill_lora_bf16":
+    elif args.entry in ("wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16"):
         segments = 1
         from paper_2407_12077_amd.workloads import make_decay_lora_inputs
         lora = make_decay_lora_inputs(cfg)
@@ -217,8 +217,12 @@ def main():
         lam = dev(lora["lam"], torch.float32)
         del x                                        # the logits are formed in the kernel
 
-        def step():
-            fn(B, T, H, N, 64, r, k, v, y, lam, b_omega, up, s_in, out, None, s_out, stream.cuda_stream)
+        if finch_c2:
+            def step():
+                fn(B, T, H, N, 64, r, k, v, y, lam, b_omega, up, s_in, out, None, s_out, stream.cuda_stream)
+        else:
+            def step():
+                fn(B, T, H, N, 64, r, k, v, y, lam, b_omega, u, s_in, out, s_out, stream.cuda_stream)
     elif finch_c2:
         segments = 1
 
@@ -253,7 +257,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
 
     abytes = algorithmic_bytes(cfg, 4 if out_f32 else 2, s_in is not None, streams_in=5 if finch_c2 else 4)
-    if args.entry == "wkv6_finch_c2_prefill_lora_bf16":
+    if args.entry in ("wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16"):
         # four bf16 streams per token-head instead of five; y once per token, the outer factor once
         abytes += -B * T * H * N * 2 + B * T * 64 * 2 + 64 * H * N * 2 + H * N * 4
     if args.entry == "wkv6_finch_c2_prefill_bf16_moments":

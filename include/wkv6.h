@@ -219,6 +219,18 @@ int wkv6_finch_c2_prefill_lora_bf16(int B, int T, int H, int N, int R,
                                     void *out, float *moments, float *state_out, void *stream);
 
 /*
+ * The Finch form (bonus u, plain key) with the same fusion: Finch's own decay is the same
+ * low-rank path (the paper takes the operators from Finch), so a Finch layer can hand over
+ * y, lambda and b_omega instead of x as well.  Arguments as for wkv6_prefill_bf16 with
+ * (y, lambda, b_omega, R) in place of x, as described for wkv6_finch_c2_prefill_lora_bf16.
+ */
+int wkv6_prefill_lora_bf16(int B, int T, int H, int N, int R,
+                           const void *r, const void *k, const void *v,
+                           const void *y, const float *lambda, const void *b_omega,
+                           const float *u, const float *state_in,
+                           void *out, float *state_out, void *stream);
+
+/*
  * Serving shapes: the same recurrence for one token (decode) or a few tokens (append) per
  * sequence and many sequences, where the cost is streaming each fp32 state through once
  * (paper: GoldFinch pre-fill is an RNN pass, so a cache is extended token by token with the

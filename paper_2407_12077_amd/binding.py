@@ -20,7 +20,7 @@ EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_s
            "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_finch_c2_prefill_bf16",
            "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_strided",
            "wkv6_finch_c2_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16_moments",
-           "wkv6_layernorm_finalize", "wkv6_finch_c2_prefill_lora_bf16",
+           "wkv6_layernorm_finalize", "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16",
            "wkv6_decode_bf16", "wkv6_finch_c2_decode_bf16", "wkv6_append_bf16",
            "wkv6_finch_c2_append_bf16", "wkv6_key_compress_bf16", "wkv6_status_string", "wkv6_version")
 
@@ -62,6 +62,8 @@ def load():
         lib.wkv6_finch_c2_prefill_bf16_moments.argtypes = [i, i, i, i] + [vp] * 10
         lib.wkv6_finch_c2_prefill_lora_bf16.restype = i
         lib.wkv6_finch_c2_prefill_lora_bf16.argtypes = [i, i, i, i, i] + [vp] * 12
+        lib.wkv6_prefill_lora_bf16.restype = i
+        lib.wkv6_prefill_lora_bf16.argtypes = [i, i, i, i, i] + [vp] * 11
         lib.wkv6_layernorm_finalize.restype = i
         lib.wkv6_layernorm_finalize.argtypes = [i, i, i, i, vp, ctypes.c_float, vp, vp]
         lib.wkv6_key_compress_bf16.restype = i
@@ -178,6 +180,12 @@ def wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, R, r, kbar, v, y, lam, b_omega, 
     _check(load().wkv6_finch_c2_prefill_lora_bf16(
         B, T, H, N, R, _ptr(r), _ptr(kbar), _ptr(v), _ptr(y), _ptr(lam), _ptr(b_omega), _ptr(uprime),
         _ptr(state_in), _ptr(out), _ptr(moments), _ptr(state_out), _stream(stream)))
+
+
+def wkv6_prefill_lora_bf16(B, T, H, N, R, r, k, v, y, lam, b_omega, u, state_in, out, state_out, stream=None):
+    _check(load().wkv6_prefill_lora_bf16(
+        B, T, H, N, R, _ptr(r), _ptr(k), _ptr(v), _ptr(y), _ptr(lam), _ptr(b_omega), _ptr(u), _ptr(state_in),
+        _ptr(out), _ptr(state_out), _stream(stream)))
 
 
 def wkv6_layernorm_finalize(B, T, H, N, moments, eps, mean_rstd, stream=None):

@@ -128,27 +128,33 @@ int wkv6_finch_c2_prefill_bf16_moments(int B, int T, int H, int N, const void* r
                true);
 }
 
-int wkv6_finch_c2_prefill_lora_bf16(int B, int T, int H, int N, int R, const void* r, const void* kbar,
-                                    const void* v, const void* y, const float* lambda, const void* b_omega,
-                                    const void* uprime, const float* state_in, void* out, float* moments,
-                                    float* state_out, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Both forms of the prefill with the decay logits formed in the kernel; `uprime` non-null selects
+// the Finch-C2 form (then `u` is unused), otherwise `u` is the Finch bonus.
+int run_lora(int B, int T, int H, int N, int R, const void* r, const void* k, const void* v, const void* y,
+             const float* lambda, const void* b_omega, const float* u, const void* uprime, bool finch_c2,
+             const float* state_in, void* out, float* moments, float* state_out, void* stream) {
     if (N != wkv6::kHeadSize || R != wkv6::kLoraRank) return WKV6_ERR_UNSUPPORTED;
     if (B < 0 || T < 0 || H < 1 || H > 262144) return WKV6_ERR_SHAPE;
+    if (!finch_c2 && !u) return WKV6_ERR_NULL;
     if (B == 0) return WKV6_OK;
     if (T > 0) {
-        if (!r || !kbar || !v || !y || !lambda || !b_omega || !uprime || !out) return WKV6_ERR_NULL;
-        if (misaligned(r) || misaligned(kbar) || misaligned(v) || misaligned(y) || misaligned(lambda) ||
+        if (!r || !k || !v || !y || !lambda || !b_omega || (finch_c2 && !uprime) || !out) return WKV6_ERR_NULL;
+        if (misaligned(r) || misaligned(k) || misaligned(v) || misaligned(y) || misaligned(lambda) ||
             misaligned(b_omega) || misaligned(uprime) || misaligned(out) || misaligned(moments))
             return WKV6_ERR_ALIGN;
     }
-    if (misaligned(state_in) || misaligned(state_out)) return WKV6_ERR_ALIGN;
+    if (misaligned(u) || misaligned(state_in) || misaligned(state_out)) return WKV6_ERR_ALIGN;
     if (static_cast<long long>(B) * H > 0x7fffffffLL) return WKV6_ERR_SHAPE;
 
     wkv6::Args a;
     a.B = B; a.T = T; a.H = H;
-    a.r = r; a.k = kbar; a.v = v; a.x = nullptr; a.u = nullptr;
-    a.finch_c2 = true;
-    a.uprime = uprime;
+    a.r = r; a.k = k; a.v = v; a.x = nullptr; a.u = u;
+    a.finch_c2 = finch_c2;
+    a.uprime = finch_c2 ? uprime : nullptr;
     a.state_in = state_in; a.out = out; a.state_out = state_out;
     a.batch_stride = static_cast<long long>(T) * H * N;
     a.segs = 1; a.T_last = T; a.seg_stride = 0; a.decay_out = nullptr; a.unit_stride = 0;
@@ -159,6 +165,25 @@ int wkv6_finch_c2_prefill_lora_bf16(int B, int T, int H, int N, int R, const voi
                                   : wkv6::launch_chunked(a, moments ? wkv6::ChunkedMode::kBf16OutLoraMoments
                                                                     : wkv6::ChunkedMode::kBf16OutLora, s);
     return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wkv6_finch_c2_prefill_lora_bf16(int B, int T, int H, int N, int R, const void* r, const void* kbar,
+                                    const void* v, const void* y, const float* lambda, const void* b_omega,
+                                    const void* uprime, const float* state_in, void* out, float* moments,
+                                    float* state_out, void* stream) {
+    return run_lora(B, T, H, N, R, r, kbar, v, y, lambda, b_omega, nullptr, uprime, true, state_in, out, moments,
+                    state_out, stream);
+}
+
+int wkv6_prefill_lora_bf16(int B, int T, int H, int N, int R, const void* r, const void* k, const void* v,
+                           const void* y, const float* lambda, const void* b_omega, const float* u,
+                           const float* state_in, void* out, float* state_out, void* stream) {
+    return run_lora(B, T, H, N, R, r, k, v, y, lambda, b_omega, u, nullptr, false, state_in, out, nullptr, state_out,
+                    stream);
 }
 
 int wkv6_layernorm_finalize(int B, int T, int H, int N, const float* moments, float eps, float* mean_rstd,
@@ -242,7 +267,7 @@ const char* wkv6_status_string(int status) {
     }
 }
 
-int wkv6_version(void) { return 420; }
+int wkv6_version(void) { return 430; }
 
 }  // extern "C"
 

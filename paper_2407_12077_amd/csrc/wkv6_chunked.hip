@@ -1024,9 +1024,10 @@ hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream) {
             if (!c2 || a.segs != 1 || !a.moments) return hipErrorInvalidValue;
             return launch_mode<3, true>(a, stream);
         default:
-            if (!c2 || a.segs != 1 || !a.y || !a.lambda || !a.bw) return hipErrorInvalidValue;
-            if (mode == ChunkedMode::kBf16OutLora) return launch_mode<4, true>(a, stream);
-            if (!a.moments) return hipErrorInvalidValue;
+            if (a.segs != 1 || !a.y || !a.lambda || !a.bw) return hipErrorInvalidValue;
+            if (mode == ChunkedMode::kBf16OutLora)
+                return c2 ? launch_mode<4, true>(a, stream) : launch_mode<4, false>(a, stream);
+            if (!c2 || !a.moments) return hipErrorInvalidValue;
             return launch_mode<5, true>(a, stream);
     }
 }

@@ -51,8 +51,9 @@ hipError_t launch_recurrent(const Args& a, bool in_bf16, bool out_bf16, hipStrea
 
 // Chunked matrix-core kernel; inputs bf16, out bf16 or fp32, or (kStateOnly) no output at all:
 // only state_out and decay_out of every unit, from r-independent work.  kBf16OutMoments: bf16 out
-// plus a.moments, Finch-C2 form and segs == 1 only.  kBf16OutLora(Moments): the same with the
-// decay logits formed in the kernel from a.y, a.lambda, a.bw instead of read from a.x.
+// plus a.moments, Finch-C2 form and segs == 1 only.  kBf16OutLora: bf16 out with the decay
+// logits formed in the kernel from a.y, a.lambda, a.bw instead of read from a.x (either form,
+// segs == 1); kBf16OutLoraMoments: that plus a.moments (Finch-C2 form).
 hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream);
 
 // Token-split support: folds the per-segment (decay, local state) pairs of every (batch, head)

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import paper_2407_12077_amd as wkv
-from oracle import decay_logits_numpy, finch_c2_oracle, head_moments_numpy
+from oracle import decay_logits_numpy, finch_c2_oracle, head_moments_numpy, wkv6_oracle
 from paper_2407_12077_amd.workloads import (CONFIGS, make_decay_lora_inputs, make_inputs, make_uprime, round_to_bf16,
                                             scaled)
 
@@ -156,3 +156,74 @@ def test_validation(gpu_device):
     wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, R, z, z, z, y, lam, bo, z, None, out, None, None)
     torch.cuda.synchronize()
     assert torch.equal(out, torch.zeros_like(out))
+
+
+# ---- the Finch form (bonus u, plain key) with the same fusion
+
+
+def run_finch_lora(inp):
+    B, T, H, N = inp["r"].shape
+    r, k, v, y, bo = (to_dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "y", "b_omega"))
+    lam, u = to_dev(inp["lam"], torch.float32), to_dev(inp["u"], torch.float32)
+    s_in = to_dev(inp.get("state_in"), torch.float32)
+    out = torch.full((B, T, H, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    s_out = torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda")
+    wkv.wkv6_prefill_lora_bf16(B, T, H, N, R, r, k, v, y, lam, bo, u, s_in, out, s_out)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64), s_out.cpu().numpy().astype(np.float64)
+
+
+def check_finch(inp):
+    B, T, H, N = inp["r"].shape
+    d = decay_logits_numpy(inp["y"], inp["lam"], inp["b_omega"], H, N)
+    o_ref, s_ref = wkv6_oracle(inp["r"], inp["k"], inp["v"], d.astype(np.float32), inp["u"], inp.get("state_in"))
+    o, s = run_finch_lora(inp)
+    eo, es = max_norm_err(o, o_ref), max_norm_err(s, s_ref)
+    assert eo <= TOL_BF16 + BF16_OUT_ROUNDING and es <= TOL_BF16, (eo, es)
+    return eo, es
+
+
+@pytest.mark.parametrize("T", [1, 31, 32, 33, 97, 200, 1000])
+def test_finch_form_lengths(gpu_device, T):
+    check_finch(inputs(scaled(CONFIGS[2], B=2, T=T, H=3)))
+
+
+@pytest.mark.parametrize("cfg_index", [2, 4, 5])
+def test_finch_form_reduced_configs(gpu_device, cfg_index):
+    dims = {2: dict(B=2, T=700, H=4), 4: dict(B=5, T=512, H=3), 5: dict(B=1, T=1500, H=6)}[cfg_index]
+    eo, es = check_finch(inputs(scaled(CONFIGS[cfg_index], **dims)))
+    print(f"fused decay path, Finch form, reduced config {cfg_index}: err_out={eo:.3e} err_state={es:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("B,T,H", [(70, 45, 4), (5, 40, 96)])
+def test_finch_form_many_units_per_workgroup(gpu_device, B, T, H):
+    check_finch(inputs(scaled(CONFIGS[4], B=B, T=T, H=H)))
+
+
+def test_finch_form_zero_activations_match_the_plain_entry(gpu_device):
+    inp = inputs(scaled(CONFIGS[2], B=2, T=100, H=3))
+    inp["y"][:] = 0.0
+    inp["lam"] = round_to_bf16(inp["lam"])
+    o, s = run_finch_lora(inp)
+    B, T, H, N = inp["r"].shape
+    x = np.broadcast_to(inp["lam"].reshape(1, 1, H, N), (B, T, H, N))
+    r, k, v, xd = (to_dev(a, torch.bfloat16) for a in (inp["r"], inp["k"], inp["v"], x))
+    u = to_dev(inp["u"], torch.float32)
+    out = torch.empty((B, T, H, N), dtype=torch.bfloat16, device="cuda")
+    s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
+    wkv.wkv6_prefill_bf16(B, T, H, N, r, k, v, xd, u, None, out, s_out)
+    torch.cuda.synchronize()
+    assert np.array_equal(o, out.float().cpu().numpy()) and np.array_equal(s, s_out.cpu().numpy())
+
+
+def test_finch_form_validation(gpu_device):
+    B, T, H, N = 1, 8, 2, 64
+    z = torch.zeros((B, T, H, N), dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros((B, T, R), dtype=torch.bfloat16, device="cuda")
+    lam = torch.zeros(H * N, dtype=torch.float32, device="cuda")
+    bo = torch.zeros((R, H * N), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty_like(z)
+    with pytest.raises(wkv.Wkv6Error):                         # the bonus is required in this form
+        wkv.wkv6_prefill_lora_bf16(B, T, H, N, R, z, z, z, y, lam, bo, None, None, out, None)
+    with pytest.raises(wkv.Wkv6Error):                         # rank
+        wkv.wkv6_prefill_lora_bf16(B, T, H, N, 128, z, z, z, y, lam, bo, lam, None, out, None)
