@@ -61,9 +61,19 @@ def cpu_baseline(cfg, inp, finch_c2=False):
     else:
         wkv6_oracle(sample["r"], sample["k"], sample["v"], sample["x"], inp["u"], s0, nthreads=cores)
     dt = time.perf_counter() - t0
+    # one thread, on the first sequence only
+    one = {n: inp[n][:1] for n in ("r", "k", "v", "x")}
+    s1 = None if inp["state_in"] is None else inp["state_in"][:1]
+    t1 = time.perf_counter()
+    if finch_c2:
+        finch_c2_oracle(one["r"], one["k"], one["v"], one["x"], inp["uprime"][:1], s1, nthreads=1)
+    else:
+        wkv6_oracle(one["r"], one["k"], one["v"], one["x"], inp["u"], s1, nthreads=1)
+    dt1 = time.perf_counter() - t1
     return {"value": nb * cfg.T / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"first {nb} of {cfg.B} sequences of the same workload "
-                      f"({nb * cfg.T * cfg.H} token-heads, fp64 sequential recurrence, {dt:.2f} s)"}
+                      f"({nb * cfg.T * cfg.H} token-heads, fp64 sequential recurrence, {dt:.2f} s)",
+            "value_single_thread": cfg.T / dt1}
 
 
 def bench_key_compress(args, torch, wkv):
