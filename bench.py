@@ -164,6 +164,8 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    from paper_2407_12077_amd.build import ensure_built
+    ensure_built()                               # compiles only when no library is there
     wkv.load()                                   # fails loudly if the HIP library is missing
     if args.entry == "wkv6_key_compress_bf16":
         return bench_key_compress(args, torch, wkv)

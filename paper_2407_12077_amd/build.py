@@ -21,5 +21,13 @@ def build(verbose=False, extra=()):
     return LIB
 
 
+def ensure_built():
+    """For the harness entry points (tests, smoke, bench): compile only when no library is there.
+    The binding itself never builds and never falls back: it raises when the library is missing."""
+    if not os.path.exists(LIB):
+        build()
+    return LIB
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # the libraries are normally built beforehand (__graft_entry__.build()); compile only if absent
+    from paper_2407_12077_amd.build import ensure_built
+    ensure_built()
+
+
 @pytest.fixture(scope="session")
 def gpu_device():
     import torch
