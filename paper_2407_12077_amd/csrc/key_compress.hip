@@ -243,10 +243,15 @@ __global__ __launch_bounds__(kKcThreads, 2) void key_compress_kernel(KcArgs a) {
     const int rows = rows_left < kBM ? static_cast<int>(rows_left) : kBM;
     const int nsteps = a.D / kBK;
     // both roles pass 2 + nsteps barriers
-    if (wave >= 4)
+    // the loaders' few instructions per step go ahead of the MFMA waves' long streams (wave
+    // priority is an issue-arbitration hint): measured 2-3 % on the benchmark shapes
+    if (wave >= 4) {
+        __builtin_amdgcn_s_setprio(2);
         kc_loader(a, lds, tid - 256, m0, n0, rows, nsteps);
-    else
+    } else {
+        __builtin_amdgcn_s_setprio(1);
         kc_worker<kOutF32>(a, lds, tid, wave, m0, n0, rows, nsteps);
+    }
 }
 
 }  // namespace
