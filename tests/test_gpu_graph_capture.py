@@ -85,3 +85,53 @@ def test_prefill_in_a_graph(gpu_device):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out_g, out_e) and torch.equal(s_g, s_e), replay
+
+
+def test_fused_layer_pieces_in_a_graph(gpu_device):
+    """The Finch-C2 prefill with the decay logits formed in the kernel and the LayerNorm partials,
+    their fold, and a key compression of as many tokens: three kernels captured as one graph."""
+    from paper_2407_12077_amd.workloads import make_decay_lora_inputs, make_key_compress_inputs, make_uprime
+    cfg = scaled(CONFIGS[4], B=3, T=130, H=4)
+    inp = make_inputs(cfg)
+    inp["uprime"] = make_uprime(cfg)
+    inp.update(make_decay_lora_inputs(cfg))
+    B, T, H, N = inp["r"].shape
+    r, k, v, up, y, bo = (to_dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "uprime", "y", "b_omega"))
+    lam, s_in = to_dev(inp["lam"], torch.float32), to_dev(inp["state_in"], torch.float32)
+    kx, kw = make_key_compress_inputs(B * T, 256)
+    hx, w_kd = to_dev(kx, torch.bfloat16), to_dev(kw, torch.bfloat16)
+
+    def fresh():
+        return (torch.full((B, T, H, N), float("nan"), dtype=torch.bfloat16, device="cuda"),
+                torch.full((B, H, T, 2), float("nan"), dtype=torch.float32, device="cuda"),
+                torch.full((B, T, 2), float("nan"), dtype=torch.float32, device="cuda"),
+                torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda"),
+                torch.full((B * T, 16), float("nan"), dtype=torch.bfloat16, device="cuda"))
+
+    def run(bufs):
+        out, mom, mr, s_out, c = bufs
+        wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, 64, r, k, v, y, lam, bo, up, s_in, out, mom, s_out)
+        wkv.wkv6_layernorm_finalize(B, T, H, N, mom, 1e-5, mr)
+        wkv.wkv6_key_compress_bf16(B * T, 256, hx, w_kd, c, wkv.WKV6_DTYPE_BF16)
+
+    eager = fresh()
+    run(eager)
+    torch.cuda.synchronize()
+    captured = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(captured)                             # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(captured)
+    for replay in range(3):
+        for t in captured:
+            t.fill_(float("nan"))                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(captured, eager):
+            assert torch.equal(a, b), replay
