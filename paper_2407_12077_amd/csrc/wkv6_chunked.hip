@@ -40,6 +40,13 @@
 // the level-1 tiles, the diagonal of the scores is zero, and the second value u' is added to the
 // fp32-staged rows before the store.
 //
+// Modes (template parameter kMode): 0 bf16 output, 1 fp32 output, 2 state only (no r, no scores,
+// no output: final state and total decay of the unit, for the token split), 3 bf16 output plus
+// the per-head partial sums of the LayerNorm over all heads (Finch-C2 output equation) taken in
+// the store phase, 4 bf16 output with the decay logits formed in the kernel from the low-rank
+// decay path (d = lambda + y B, consumers' MFMAs, handed to phase D through LDS) instead of
+// read as x, 5 both.
+//
 // LDS tiles are [token][channel] fp16 with a 160-byte row stride, the stride at which the
 // 16-byte row reads of MFMA operands run at the full rate of the gfx950 LDS; operands whose
 // contraction index is the token (k^T V, A V) are fetched with the transposing read
