@@ -62,7 +62,8 @@ typedef enum {
     WKV6_ERR_SHAPE = 2,       /* negative size, H < 1, stride too small, overflow of the grid */
     WKV6_ERR_UNSUPPORTED = 3, /* N != 64, or an unknown dtype code */
     WKV6_ERR_LAUNCH = 4,      /* hipGetLastError() after the launch was not hipSuccess */
-    WKV6_ERR_ALIGN = 5        /* a tensor base or the batch stride is not 16-byte aligned */
+    WKV6_ERR_ALIGN = 5,       /* a tensor base or the batch stride is not 16-byte aligned */
+    WKV6_ERR_WORKSPACE = 6    /* the shape needs more scratch memory than the library's fixed buffer */
 } wkv6_status;
 
 typedef enum {
@@ -112,6 +113,27 @@ int wkv6_prefill_bf16_split(int B, int T, int H, int N,
                             const float *u, const float *state_in,
                             void *out, float *state_out, int out_dtype, int segments,
                             void *workspace, long long workspace_bytes, void *stream);
+
+/*
+ * wkv6_prefill_bf16_split for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * per-segment states live in a buffer of WKV6_SPLIT_NOALLOC_BYTES that is part of the library's
+ * code object on every GPU it runs on, for the life of the process.  The call allocates and
+ * frees nothing.  Shapes with wkv6_split_workspace_bytes(B,T,H,N,segments) above that size
+ * return WKV6_ERR_WORKSPACE and enqueue nothing (B*segments*H <= 504 fits; config 3 with 8
+ * segments uses 4.3 MB).  All calls on one GPU share that buffer, whatever their stream: calls
+ * that overlap in time on one GPU race on it, so order them on one stream (or with events).
+ * Nothing in it has to start at zero (pass 1 writes every entry the later passes read), and it
+ * keeps the last call's contents.  The buffer's address is looked up on a GPU's first call (one
+ * hipGetSymbolAddress per device, no allocation); make that first call outside stream capture.
+ * Arguments, results and errors otherwise as for wkv6_prefill_bf16_split.
+ */
+#define WKV6_SPLIT_NOALLOC_BYTES (8ll << 20)
+int wkv6_prefill_bf16_split_noalloc(int B, int T, int H, int N,
+                                    const void *r, const void *k, const void *v, const void *x,
+                                    const float *u, const float *state_in,
+                                    void *out, float *state_out, int out_dtype, int segments,
+                                    void *stream);
 
 /* Bytes of workspace wkv6_prefill_bf16_split needs for this shape (-1 for invalid arguments). */
 long long wkv6_split_workspace_bytes(int B, int T, int H, int N, int segments);

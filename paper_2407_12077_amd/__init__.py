@@ -5,6 +5,6 @@ from .binding import (  # noqa: F401
     wkv6_finch_c2_prefill_bf16_moments, wkv6_finch_c2_prefill_bf16_split, wkv6_finch_c2_prefill_lora_bf16, wkv6_layernorm_finalize,
     wkv6_key_compress_bf16,
     wkv6_finch_c2_prefill_bf16_f32out, wkv6_finch_c2_prefill_bf16_strided, wkv6_prefill_bf16,
-    wkv6_prefill_bf16_f32out, wkv6_prefill_bf16_recurrent, wkv6_prefill_lora_bf16, wkv6_prefill_bf16_split,
+    wkv6_prefill_bf16_f32out, wkv6_prefill_bf16_recurrent, wkv6_prefill_lora_bf16, wkv6_prefill_bf16_split, wkv6_prefill_bf16_split_noalloc,
     wkv6_prefill_bf16_strided, wkv6_prefill_f32, wkv6_split_segments, wkv6_split_workspace_bytes,
     wkv6_version)

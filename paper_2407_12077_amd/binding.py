@@ -17,6 +17,7 @@ WKV6_DTYPE_F32 = 1
 
 EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_strided",
            "wkv6_prefill_f32", "wkv6_prefill_bf16_recurrent", "wkv6_prefill_bf16_split",
+           "wkv6_prefill_bf16_split_noalloc",
            "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_finch_c2_prefill_bf16",
            "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_strided",
            "wkv6_finch_c2_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16_moments",
@@ -70,6 +71,8 @@ def load():
         lib.wkv6_key_compress_bf16.argtypes = [ll, i, vp, vp, vp, i, vp]
         lib.wkv6_prefill_bf16_split.restype = i
         lib.wkv6_prefill_bf16_split.argtypes = common + [i, i, vp, ll, vp]
+        lib.wkv6_prefill_bf16_split_noalloc.restype = i
+        lib.wkv6_prefill_bf16_split_noalloc.argtypes = common + [i, i, vp]
         lib.wkv6_finch_c2_prefill_bf16_split.restype = i
         lib.wkv6_finch_c2_prefill_bf16_split.argtypes = common + [i, i, vp, ll, vp]
         lib.wkv6_split_workspace_bytes.restype = ll
@@ -128,6 +131,12 @@ def wkv6_prefill_bf16_split(B, T, H, N, r, k, v, x, u, state_in, out, state_out,
                             segments, workspace, workspace_bytes, stream=None):
     _call("wkv6_prefill_bf16_split", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream,
           int(out_dtype), int(segments), _ptr(workspace), ctypes.c_longlong(workspace_bytes))
+
+
+def wkv6_prefill_bf16_split_noalloc(B, T, H, N, r, k, v, x, u, state_in, out, state_out, out_dtype,
+                                    segments, stream=None):
+    _call("wkv6_prefill_bf16_split_noalloc", B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream,
+          int(out_dtype), int(segments))
 
 
 def wkv6_finch_c2_prefill_bf16_split(B, T, H, N, r, kbar, v, x, uprime, state_in, out, state_out,

@@ -4,6 +4,7 @@
 #include "wkv6_launch.h"
 
 #include <cstdint>
+#include <mutex>
 
 namespace {
 
@@ -263,6 +264,7 @@ const char* wkv6_status_string(int status) {
         case WKV6_ERR_UNSUPPORTED: return "unsupported head size or dtype";
         case WKV6_ERR_LAUNCH: return "kernel launch failed";
         case WKV6_ERR_ALIGN: return "pointer or stride not 16-byte aligned";
+        case WKV6_ERR_WORKSPACE: return "shape needs more scratch than the library holds";
         default: return "unknown status";
     }
 }
@@ -317,7 +319,34 @@ long long wkv6_split_workspace_bytes(int B, int T, int H, int N, int segments) {
 
 }  // extern "C"
 
+// ---- library-owned scratch for the entry point that may not allocate
+
 namespace {
+
+// Per-segment local states and decay totals of wkv6_prefill_bf16_split_noalloc.  Every GPU the
+// library runs on holds its own copy of this array, at its own address, until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the device address it
+// returns is what kernels, copies and fills must be given.
+constexpr long long kScratchBytes = 8ll << 20;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int scratch_of_current_device(void** ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return WKV6_ERR_LAUNCH;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return WKV6_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return WKV6_OK;
+}
 
 int run_split(int B, int T, int H, int N, const void* r, const void* k, const void* v, const void* x,
               const float* u, const void* uprime, bool finch_c2, const float* state_in, void* out,
@@ -377,6 +406,19 @@ int wkv6_prefill_bf16_split(int B, int T, int H, int N, const void* r, const voi
                             long long workspace_bytes, void* stream) {
     return run_split(B, T, H, N, r, k, v, x, u, nullptr, false, state_in, out, state_out, out_dtype,
                      segments, workspace, workspace_bytes, stream);
+}
+
+int wkv6_prefill_bf16_split_noalloc(int B, int T, int H, int N, const void* r, const void* k, const void* v,
+                                    const void* x, const float* u, const float* state_in, void* out,
+                                    float* state_out, int out_dtype, int segments, void* stream) {
+    const long long need = wkv6_split_workspace_bytes(B, T, H, N, segments);
+    if (need < 0) return N != wkv6::kHeadSize ? WKV6_ERR_UNSUPPORTED : WKV6_ERR_SHAPE;
+    if (need > kScratchBytes) return WKV6_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int status = scratch_of_current_device(&ws);
+    if (status != WKV6_OK) return status;
+    return run_split(B, T, H, N, r, k, v, x, u, nullptr, false, state_in, out, state_out, out_dtype,
+                     segments, ws, kScratchBytes, stream);
 }
 
 int wkv6_finch_c2_prefill_bf16_split(int B, int T, int H, int N, const void* r, const void* kbar,

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_status_strings():
     assert wkv.wkv6_version() >= 100
     assert wkv.status_string(0) == "ok"
-    for code in range(1, 6):
+    for code in range(1, 7):
         assert wkv.status_string(code) not in ("ok", "unknown status")
     assert wkv.status_string(99) == "unknown status"
 
