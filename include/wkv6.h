@@ -35,15 +35,27 @@
  * different streams may overlap.
  *
  * Decay logits: any finite x, and x = -inf (w = 1) and x = +inf (w = 0), are
- * handled exactly as the formula says: the chunked kernels only ever form
- * products of decays (all <= 1), never a reciprocal, so there is no clamp.
+ * accepted without a clamp: the chunked kernels only ever form products of
+ * decays (all <= 1), never a reciprocal or a positive exponent, so nothing
+ * overflows.  The Finch-C2 key factor 1 - w is formed without subtracting
+ * nearly equal numbers (a series in exp(x) when w is close to 1).
  *
  * Value range of the bf16 entry points: the dense contractions run on the
  * matrix cores with fp16 operands and fp32 accumulation; r, k, v, the products
  * r*u and k*u, the intra-chunk scores and the running state must stay below
  * 65504 in magnitude (larger values saturate to that bound: results stay
- * finite but are those of the clamped operands).  The fp32 entry point has no
- * such limit.
+ * finite but are those of the clamped operands).  At the small end, an fp16
+ * operand below 2^-14 = 6.1e-5 in magnitude -- r, k or v times the product of
+ * decays that scales it inside a 32-token chunk, and in the Finch-C2 form the
+ * key kbar (1 - w) itself -- is held to an absolute 2^-25 instead of a relative
+ * 2^-11, and below 2^-25 it is zero.  Against the largest value of a (batch,
+ * head) unit this is far inside the tolerance; a row of the output or of the
+ * state whose own values are that small is accurate to that absolute step
+ * only (each output value: at most 2^-14 (max|r| + max|k|) max|v| + 2^-19
+ * (1 + max|r|) max|S|).  Finch-C2 channels with decay logits below about -10
+ * (1 - w < 5e-5) are the case that matters: scale kbar so that kbar (1 - w)
+ * stays above 2^-14 if those state rows are needed to full relative accuracy.
+ * The fp32 entry point and the decode entry points have no such limits.
  *
  * Errors: every entry point returns a wkv6_status.  Arguments are validated
  * before anything is enqueued; on a non-zero status nothing was launched,

@@ -134,6 +134,16 @@ __device__ __forceinline__ float decay_of(float x) {
     return __builtin_amdgcn_exp2f(-e);
 }
 
+// Finch-C2 key factor 1 - w = 1 - exp(-e), e = exp(x), without the cancellation of the plain
+// subtraction for long-memory channels (w close to 1): below e = 2^-5 the alternating series
+// e (1 - e/2 + e^2/6 - e^3/24), whose first dropped term is under 1e-8 of the result there;
+// above it the subtraction loses at most five bits of an fp32 value.
+__device__ __forceinline__ float one_minus_decay(float x, float w) {
+    const float e = __builtin_amdgcn_exp2f(x * kLog2e);
+    const float series = e * __builtin_fmaf(e, __builtin_fmaf(e, __builtin_fmaf(e, -1.f / 24.f, 1.f / 6.f), -0.5f), 1.f);
+    return e < 0.03125f ? series : 1.f - w;
+}
+
 __device__ __forceinline__ half8 lds_read_h8(const char* lds, int byte_off) {
     return *reinterpret_cast<const half8*>(lds + byte_off);
 }
@@ -355,6 +365,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                 if (t0 + 4 * g8 + s >= T) cur.x[s] = 0xff80ff80u;      // bf16 -inf, twice
         }
         float w[2][4];
+        [[maybe_unused]] float omw[2][4];       // Finch-C2: 1 - w
         if constexpr (kLora) {
             // the chunk's logits were left in LDS by the consumers one window ago: this thread's
             // 4 tokens of its two channels
@@ -367,12 +378,20 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                 const bool past = t0 + 4 * g8 + s >= T;          // tokens past the end: w = 1
                 w[0][s] = past ? 1.f : decay_of(d0[s]);
                 w[1][s] = past ? 1.f : decay_of(d1[s]);
+                if constexpr (kC2) {
+                    omw[0][s] = one_minus_decay(d0[s], w[0][s]);       // past the end the key is zero
+                    omw[1][s] = one_minus_decay(d1[s], w[1][s]);
+                }
             }
         } else {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 w[0][s] = decay_of(bf16_lo(cur.x[s]));
                 w[1][s] = decay_of(bf16_hi(cur.x[s]));
+                if constexpr (kC2) {
+                    omw[0][s] = one_minus_decay(bf16_lo(cur.x[s]), w[0][s]);
+                    omw[1][s] = one_minus_decay(bf16_hi(cur.x[s]), w[1][s]);
+                }
             }
         }
         // products of decays inside the group, fp32: prefix of token 2 and 3, suffix of token 1
@@ -394,7 +413,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         for (int s = 0; s < 4; ++s) {
             rh[s] = pack_h2(bf16_lo(cur.r[s]), bf16_hi(cur.r[s]));
             if constexpr (kC2)      // Finch-C2: k = kbar (1 - w), the factor applied in fp32
-                kh[s] = pack_h2(bf16_lo(cur.k[s]) * (1.f - w[0][s]), bf16_hi(cur.k[s]) * (1.f - w[1][s]));
+                kh[s] = pack_h2(bf16_lo(cur.k[s]) * omw[0][s], bf16_hi(cur.k[s]) * omw[1][s]);
             else
                 kh[s] = pack_h2(bf16_lo(cur.k[s]), bf16_hi(cur.k[s]));
             pr.vt[s] = pack_h2(bf16_lo(cur.v[s]), bf16_hi(cur.v[s]));

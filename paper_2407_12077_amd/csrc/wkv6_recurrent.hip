@@ -70,7 +70,8 @@ __global__ __launch_bounds__(64) void recurrent_kernel(Args a) {
     for (int t = 0; t < a.T; ++t) {
         const float r_cur = rj, v_cur = vj, p_cur = pj;
         const float w_cur = expf(-expf(xj));
-        const float k_cur = kC2 ? kj * (1.f - w_cur) : kj;
+        // Finch-C2 key factor 1 - w = -expm1(-exp(x)): no cancellation for decays close to 1
+        const float k_cur = kC2 ? kj * -expm1f(-expf(xj)) : kj;
         const long long idx_cur = idx;
         idx += tok_stride;
         if (t + 1 < a.T) {                     // next token's loads overlap this token's math

@@ -20,6 +20,38 @@ def max_norm_err(got, ref):
     return float(np.abs(got - ref).max() / denom)
 
 
+def error_report(got, ref, kind):
+    """Every error figure the parity tests print for one tensor against the oracle's:
+
+    global   max |got - ref| / max |ref| over the whole tensor (the gated definition)
+    unit     the same ratio taken per (batch, head) unit, worst unit (gated at the same tolerance:
+             a unit whose values are small next to the tensor's largest cannot hide)
+    row      per token row (out) or per key row (state): max over the 64 channels of |got - ref| over
+             the max of |ref| in that row, worst row (reported; rows of near-zero reference values
+             make it large without meaning anything, so it is not gated)
+    rel_l2   ||got - ref||_2 / ||ref||_2
+
+    kind: "out" for [B, T, H, N] tensors, "state" for [B, H, N, N]."""
+    ref = np.asarray(ref, dtype=np.float64)
+    diff = np.abs(np.asarray(got, dtype=np.float64) - ref)
+    aref = np.abs(ref)
+    unit_axes = (1, 3) if kind == "out" else (2, 3)
+    d_row, r_row = diff.max(axis=3), aref.max(axis=3)
+    unit_axis_of_rows = 1 if kind == "out" else 2
+    d_unit, r_unit = d_row.max(axis=unit_axis_of_rows), r_row.max(axis=unit_axis_of_rows)
+    assert d_unit.shape == diff.max(axis=unit_axes).shape
+    tiny = np.finfo(np.float64).tiny
+    l2 = float(np.sqrt(np.square(diff).sum() / max(np.square(ref).sum(), tiny)))
+    return {"global": float(d_unit.max() / max(r_unit.max(), tiny)),
+            "unit": float((d_unit / np.maximum(r_unit, tiny)).max()),
+            "row": float((d_row / np.maximum(r_row, tiny)).max()),
+            "rel_l2": l2}
+
+
+def fmt_report(rep):
+    return " ".join(f"{k}={v:.3e}" for k, v in rep.items())
+
+
 def to_dev(a, dtype):
     if a is None:
         return None
