@@ -47,10 +47,17 @@
 // decay path (d = lambda + y B, consumers' MFMAs, handed to phase D through LDS) instead of
 // read as x, 5 both.
 //
-// LDS tiles are [token][channel] fp16 with a 160-byte row stride, the stride at which the
-// 16-byte row reads of MFMA operands run at the full rate of the gfx950 LDS; operands whose
-// contraction index is the token (k^T V, A V) are fetched with the transposing read
-// ds_read_b64_tr_b16 instead of keeping transposed copies.
+// LDS tiles whose contraction index is the channel (scores, inter-chunk read) are [token][channel]
+// fp16 with a 160-byte row stride; the two tiles whose contraction index is the token (k^T V, A V:
+// scaled keys and values) are stored transposed, [channel][token] with a 96-byte row stride and
+// the 16-byte granules of a row XOR-swizzled by two row bits.  With these layouts every MFMA
+// operand is one 16-byte row read at the full rate of the gfx950 LDS (measured 254 B/clk), and a
+// producer thread, which owns four consecutive tokens of a channel pair, writes a transposed
+// tile with two 8-byte stores instead of four 4-byte ones (LDS stores cost about 4 clk per
+// instruction up to 4 bytes per lane and 6-8 clk for 8 bytes: the kernel is bound by the LDS
+// pipeline, and stores are its slow half).  The output tile is produced transposed by swapping
+// the operands of the consumers' MFMAs, so that a lane holds four consecutive value channels of
+// one token and stages them with one store.
 #include "wkv6_launch.h"
 
 #include <type_traits>
@@ -70,6 +77,8 @@ constexpr int kProducerGroups = 3;         // 4 waves each
 constexpr int kThreads = 64 * (4 * kProducerGroups + 4);
 constexpr int kRow = 160;                  // fp16 tile row stride in bytes (64 halfs + 16 pad)
 constexpr int kTile = kChunk * kRow;       // one [32 tokens][64 channels] tile
+constexpr int kRowT = 96;                  // transposed tile [channel][32 tokens]: 64 B + 32 pad
+constexpr int kTileT = 64 * kRowT;
 constexpr int kORowF32 = 68;               // output staging row stride, fp32 mode (floats)
 constexpr int kORowBf16 = 72;              // output staging row stride, bf16 mode (halfs)
 
@@ -82,11 +91,11 @@ enum : int {
     kQ1 = 4 * kTile,       // level 1 and bonus, query side: r (odd tokens), r*u (even tokens)
     kK1 = 5 * kTile,       // level 1 and bonus, key side:   k (even tokens), k*u (odd tokens)
     kRT = 6 * kTile,       // r * W(t,-1), channel order permuted to match the state registers
-    kKT = 7 * kTile,       // k * W(32,i)
-    kVT = 8 * kTile,       // v as fp16
-    kA0 = 9 * kTile,       // scores A[t][i], contraction over channels 0..31
-    kA1 = 10 * kTile,      // scores A[t][i], contraction over channels 32..63
-    kG = 11 * kTile,                       // per 4-token group decay products [8][64] fp32
+    kKT = 7 * kTile,       // k * W(32,i), transposed: [key channel][token]
+    kVT = kKT + kTileT,    // v as fp16, transposed: [value channel][token]
+    kA0 = kVT + kTileT,    // scores A[t][i], contraction over channels 0..31
+    kA1 = kA0 + kTile,     // scores A[t][i], contraction over channels 32..63
+    kG = kA1 + kTile,                      // per 4-token group decay products [8][64] fp32
     kD = kG + 8 * 64 * 4,                  // whole-chunk decay product [64] fp32
     kO = kD + 64 * 4,                      // output staging [32 tokens][64]
     kBuf = (kO + kChunk * kORowF32 * 4 + 1023) / 1024 * 1024,
@@ -121,8 +130,12 @@ __device__ __forceinline__ unsigned mul_h2(unsigned a, unsigned b) {
     return __builtin_bit_cast(unsigned, __builtin_bit_cast(half2v, a) * __builtin_bit_cast(half2v, b));
 }
 
-__device__ __forceinline__ unsigned short bf16_bits(float a) {
-    return __builtin_bit_cast(unsigned short, static_cast<__bf16>(a));
+// two floats to a bf16 pair (round to nearest even), one packed conversion
+__device__ __forceinline__ unsigned pack_bf2(float a, float b) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    const float2v f = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
 }
 
 // w = exp(-exp(x)) through two base-2 exponentials (x=-inf -> 1, x=+inf -> 0):
@@ -151,20 +164,24 @@ __device__ __forceinline__ void lds_write_u32(char* lds, int byte_off, unsigned 
     *reinterpret_cast<unsigned*>(lds + byte_off) = val;
 }
 
-// Transposing LDS read.  Within each group of 16 lanes, lane i passes the address of the
-// 4 halfs M[i>>2][4*(i&3) .. +3] of a row-major block M (4 rows x 16 columns) and receives
-// M[0..3][i]: four consecutive rows of "its" column.  Two of them give the 8 token-slots a
-// lane feeds to the MFMA when the contraction index is the tile's row (token) index.
-__device__ __forceinline__ half4 lds_read_tr(const char* lds, int byte_off) {
-    typedef short short4v __attribute__((ext_vector_type(4)));
-    typedef short4v __attribute__((address_space(3))) * lds_s4_ptr;
-    return __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(lds + byte_off)));
+// Byte offset, inside a transposed tile, of the 16-byte granule `granule` (tokens 8*granule .. +7)
+// of row `row` (a channel).  The XOR with two row bits makes the producers' 8-byte stores (32
+// lanes on 32 different rows, two lanes per granule) and the consumers' 16-byte reads (16
+// consecutive rows) both run without bank conflicts beyond the store pipeline's own rate.
+__device__ __forceinline__ int tile_t_off(int row, int granule) {
+    return row * kRowT + ((granule ^ ((row >> 2) & 3)) << 4);
 }
-__device__ __forceinline__ half8 lds_read_tr8(const char* lds, int byte_off) {
-    const half4 lo = lds_read_tr(lds, byte_off);
-    const half4 hi = lds_read_tr(lds, byte_off + 4 * kRow);
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+// Score tiles A[t][i] (rows of 64 bytes, stride kRow): granule `granule` (keys 8*granule .. +7) of
+// token row t, swizzled by one row bit for the 8-byte score stores.
+__device__ __forceinline__ int score_off(int t, int granule) {
+    return t * kRow + ((granule ^ ((t >> 2) & 1)) << 4);
 }
+__device__ __forceinline__ void lds_write_u64(char* lds, int byte_off, unsigned lo, unsigned hi) {
+    *reinterpret_cast<uint2*>(lds + byte_off) = make_uint2(lo, hi);
+}
+// low halves / high halves of two packed fp16 pairs as one pair
+__device__ __forceinline__ unsigned lo_halves(unsigned a, unsigned b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ unsigned hi_halves(unsigned a, unsigned b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 __device__ __forceinline__ float4v mfma(half8 a, half8 b, float4v c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
@@ -173,9 +190,11 @@ __device__ __forceinline__ float4v mfma(half8 a, half8 b, float4v c) {
 // Cache policy of the streams that are touched exactly once (r, k, v, x, u', out): the
 // non-temporal bit, so they do not displace each other in the caches on their way through.
 constexpr int kStreamOnce = 2;
-__device__ __forceinline__ void store_once(void* p, uint4v q) {
-    __builtin_nontemporal_store(q, static_cast<uint4v*>(p));
-}
+// Cache policy of the output rows: scope bit sc1 without the non-temporal bit, i.e. written
+// through the XCD's L2 as they are produced instead of lingering there as dirty lines.  Measured
+// with a streaming probe of this layout (four non-temporal input streams, one output stream of
+// 128-byte rows 4 KiB apart): 130.7 us against 135.8 us with non-temporal stores.
+constexpr int kStoreThrough = 16;
 
 struct Raw {           // one chunk's inputs of a producer thread: 4 tokens x one channel pair
     unsigned r[4], k[4], v[4], x[4];
@@ -295,7 +314,8 @@ struct Cursor {
 // What a producer thread carries from phase D (where it digests the raw inputs of its chunk)
 // to phase T (where the other groups' decay totals are known and the tiles are written).
 struct Prep {
-    unsigned z2[4], q1[4], k1[4], vt[4];                  // finished fp16 pairs, one per token
+    unsigned z2[4], q1[4], k1[4];                         // finished fp16 pairs (two channels), one per token
+    unsigned vt[4];            // v as fp16 pairs of consecutive tokens: [2*channel + token pair]
     unsigned rp[4];            // r * prefix product inside the group, fp16 pair (2 channels)
     unsigned ks[4];            // k * suffix product inside the group, fp16 pair
 };
@@ -416,8 +436,12 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                 kh[s] = pack_h2(bf16_lo(cur.k[s]) * omw[0][s], bf16_hi(cur.k[s]) * omw[1][s]);
             else
                 kh[s] = pack_h2(bf16_lo(cur.k[s]), bf16_hi(cur.k[s]));
-            pr.vt[s] = pack_h2(bf16_lo(cur.v[s]), bf16_hi(cur.v[s]));
         }
+        // v goes to a transposed tile: pairs of consecutive tokens of one channel
+        pr.vt[0] = pack_h2(bf16_lo(cur.v[0]), bf16_lo(cur.v[1]));
+        pr.vt[1] = pack_h2(bf16_lo(cur.v[2]), bf16_lo(cur.v[3]));
+        pr.vt[2] = pack_h2(bf16_hi(cur.v[0]), bf16_hi(cur.v[1]));
+        pr.vt[3] = pack_h2(bf16_hi(cur.v[2]), bf16_hi(cur.v[3]));
         pr.rp[0] = rh[0];
         pr.rp[1] = mul_h2(rh[1], pack_h2(w[0][0], w[1][0]));
         pr.rp[2] = mul_h2(rh[2], pack_h2(p2[0], p2[1]));
@@ -466,7 +490,11 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             lds_write_u32(lds, tile + nat0 + 2 * kRow, v2);
             lds_write_u32(lds, tile + nat0 + 3 * kRow, v3);
         };
-        put4(kVT, pr.vt[0], pr.vt[1], pr.vt[2], pr.vt[3]);
+        // transposed tiles: this thread's 4 tokens of channel 2cp (and 2cp+1) are 8 contiguous bytes
+        const int tr0 = tile_t_off(2 * cp, wq) + 8 * hl;          // tokens 4*g8 .. +3 = half hl of granule wq
+        const int tr1 = tile_t_off(2 * cp + 1, wq) + 8 * hl;
+        lds_write_u64(lds, kVT + tr0, pr.vt[0], pr.vt[1]);
+        lds_write_u64(lds, kVT + tr1, pr.vt[2], pr.vt[3]);
         if constexpr (!kStateOnly) {
             // level 4: the even group of an 8-block holds keys, the odd one queries
             put4(kZ4, q4 ? pr.rp[0] : pr.ks[0], q4 ? pr.rp[1] : pr.ks[1], q4 ? pr.rp[2] : pr.ks[2],
@@ -504,7 +532,12 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         const unsigned h_kt = pack_h2(m_kt[0], m_kt[1]);
         const unsigned h16 = pack_h2(m16[0], m16[1]);
         const unsigned h8 = pack_h2(m8[0], m8[1]);
-        put4(kKT, mul_h2(pr.ks[0], h_kt), mul_h2(pr.ks[1], h_kt), mul_h2(pr.ks[2], h_kt), mul_h2(pr.ks[3], h_kt));
+        {
+            const unsigned k0 = mul_h2(pr.ks[0], h_kt), k1 = mul_h2(pr.ks[1], h_kt);
+            const unsigned k2 = mul_h2(pr.ks[2], h_kt), k3 = mul_h2(pr.ks[3], h_kt);
+            lds_write_u64(lds, kKT + tr0, lo_halves(k0, k1), lo_halves(k2, k3));
+            lds_write_u64(lds, kKT + tr1, hi_halves(k0, k1), hi_halves(k2, k3));
+        }
         if constexpr (!kStateOnly) {
             const unsigned* z16 = kQ16 ? pr.rp : pr.ks;
             const unsigned* z8 = kQ8 ? pr.rp : pr.ks;
@@ -551,14 +584,15 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
             const float val = d >= 8 ? acc8[e] : d >= 4 ? acc4[e] : d >= 2 ? acc2[e] : acc1[e];
             sel[e] = (kC2 ? i >= t : i > t) ? 0.f : val;    // Finch-C2 has no diagonal term
         }
-        *reinterpret_cast<uint2*>(lds + at + (16 * q + l16) * kRow + (16 * q + 4 * g4) * 2) =
+        // keys 16q + 4*g4 .. +3 of token row 16q + l16: half (g4 & 1) of granule 2q + (g4 >> 1)
+        *reinterpret_cast<uint2*>(lds + at + score_off(16 * q + l16, 2 * q + (g4 >> 1)) + 8 * (g4 & 1)) =
             make_uint2(pack_h2(sel[0], sel[1]), pack_h2(sel[2], sel[3]));
         if (q == 0) {
             const int rq = (16 + l16) * kRow + 16 * g4 + 64 * kk;
             const half8 zq = lds_read_h8(lds, kZ16 + rq);
             const half8 zk = lds_read_h8(lds, kZ16 + rq - 16 * kRow);
             const float4v acc = mfma(zk, zq, zero);
-            *reinterpret_cast<uint2*>(lds + at + (16 + l16) * kRow + (4 * g4) * 2) =
+            *reinterpret_cast<uint2*>(lds + at + score_off(16 + l16, g4 >> 1) + 8 * (g4 & 1)) =
                 make_uint2(pack_h2(acc[0], acc[1]), pack_h2(acc[2], acc[3]));
         }
     };
@@ -585,11 +619,22 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                                                     up_voff, 0, kStreamOnce));
         }
     };
+    // Output rows leave through a raw buffer descriptor that starts at the chunk's first row and ends
+    // with the unit's last token: rows past the end of the sequence are dropped by the bounds check.
+    constexpr int kOutElem = kOutF32 ? 4 : 2;
+    [[maybe_unused]] const long long out_row_bytes = tok_stride * kOutElem;
+    [[maybe_unused]] const long long out_span = static_cast<long long>(T - 1) * out_row_bytes + kHeadSize * kOutElem;
+    [[maybe_unused]] const int out_voff = static_cast<int>(srow * out_row_bytes + scol * kOutElem);
+    [[maybe_unused]] const char* out_base = static_cast<const char*>(a.out) + un.base0 * kOutElem;
     auto store_rows = [&](int g, const Cursor<kMulti>& at) {   // g: position in the sequence (LDS parity)
         const char* lds = lds_all + (g & 1) * kBuf;
         const int t = at.c * kChunk + srow;
+        const __amdgpu_buffer_rsrc_t ro = chunk_rsrc(out_base + at.unit_elems(un) * kOutElem,
+                                                     static_cast<long long>(at.c) * kChunk * out_row_bytes, out_span);
+        auto put = [&](uint4v q, int byte) {
+            __builtin_amdgcn_raw_buffer_store_b128(q, ro, out_voff + byte, 0, kStoreThrough);
+        };
         if (t < T) {
-            const long long e = un.base0 + at.unit_elems(un) + static_cast<long long>(t) * tok_stride + scol;
             if constexpr (kStageF32) {
                 const float4* src = reinterpret_cast<const float4*>(lds + kO + (srow * kORowF32 + scol) * 4);
                 float4 q0 = src[0], q1 = src[1];
@@ -625,20 +670,18 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                     }
                 }
                 if constexpr (kOutF32) {
-                    float* dst = static_cast<float*>(a.out) + e;
-                    store_once(dst, __builtin_bit_cast(uint4v, q0));
-                    store_once(dst + 4, __builtin_bit_cast(uint4v, q1));
+                    put(__builtin_bit_cast(uint4v, q0), 0);
+                    put(__builtin_bit_cast(uint4v, q1), 16);
                 } else {
                     uint4v q;
-                    q.x = bf16_bits(q0.x) | (static_cast<unsigned>(bf16_bits(q0.y)) << 16);
-                    q.y = bf16_bits(q0.z) | (static_cast<unsigned>(bf16_bits(q0.w)) << 16);
-                    q.z = bf16_bits(q1.x) | (static_cast<unsigned>(bf16_bits(q1.y)) << 16);
-                    q.w = bf16_bits(q1.z) | (static_cast<unsigned>(bf16_bits(q1.w)) << 16);
-                    store_once(static_cast<unsigned short*>(a.out) + e, q);
+                    q.x = pack_bf2(q0.x, q0.y);
+                    q.y = pack_bf2(q0.z, q0.w);
+                    q.z = pack_bf2(q1.x, q1.y);
+                    q.w = pack_bf2(q1.z, q1.w);
+                    put(q, 0);
                 }
             } else {
-                const uint4v q = *reinterpret_cast<const uint4v*>(lds + kO + (srow * kORowBf16 + scol) * 2);
-                store_once(static_cast<unsigned short*>(a.out) + e, q);
+                put(*reinterpret_cast<const uint4v*>(lds + kO + (srow * kORowBf16 + scol) * 2), 0);
             }
         }
     };
@@ -769,11 +812,11 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
         fetch_state(S, 0);
 
     float dtot = 1.f;   // product of all decays so far, key channel `lane` (only with decay_out)
-    float4v o[2];       // output rows of the chunk whose state chain ran last: 2 t-blocks x 4 rows
-    half8 vt;           // its V operand: 32 tokens x this lane's column
-    // byte offset of this lane's share of a transposing read: token row (8*g4 + (l16>>2)),
-    // 4-channel granule (l16&3) of a 16-channel block
-    const int tr_lane = (8 * g4 + (l16 >> 2)) * kRow + 8 * (l16 & 3);
+    // Output of the chunk whose state chain ran last, transposed: o[tq][e] belongs to token
+    // 16*tq + l16 and value channel 16*cw + 4*g4 + e (the state is the A operand and the token rows
+    // the B operand of the MFMAs below), so a lane's four values are contiguous in the output row.
+    float4v o[2];
+    half8 vt;           // V^T operand of that chunk: this lane's value channel, tokens 8*g4 .. +7
 
     const int total = un.count * un.nchunks;
     const int nwin = (total + 6) / 3 * 3;
@@ -846,19 +889,17 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
             char* lds = lds_all + ((n - 3) & 1) * kBuf;
 #pragma unroll
             for (int tq = 0; tq < 2; ++tq) {
-                const int off = (16 * tq + l16) * kRow + 16 * g4;
+                const int off = score_off(16 * tq + l16, g4);
                 const half8 a0 = lds_read_h8(lds, kA0 + off);
                 const half8 a1 = lds_read_h8(lds, kA1 + off);
-                o[tq] = mfma(a0, vt, o[tq]);
-                o[tq] = mfma(a1, vt, o[tq]);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int row = 16 * tq + 4 * g4 + e;
-                    if constexpr (kOutF32 || kC2)
-                        *reinterpret_cast<float*>(lds + kO + (row * kORowF32 + j) * 4) = o[tq][e];
-                    else
-                        *reinterpret_cast<unsigned short*>(lds + kO + (row * kORowBf16 + j) * 2) = bf16_bits(o[tq][e]);
-                }
+                o[tq] = mfma(vt, a0, o[tq]);
+                o[tq] = mfma(vt, a1, o[tq]);
+                const int row = 16 * tq + l16, col = 16 * cw + 4 * g4;
+                if constexpr (kOutF32 || kC2)
+                    *reinterpret_cast<float4v*>(lds + kO + (row * kORowF32 + col) * 4) = o[tq];
+                else
+                    *reinterpret_cast<uint2*>(lds + kO + (row * kORowBf16 + col) * 2) =
+                        make_uint2(pack_bf2(o[tq][0], o[tq][1]), pack_bf2(o[tq][2], o[tq][3]));
             }
         }
         if (n >= 2 && n - 2 < total) {
@@ -874,7 +915,7 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
                 dtot = 1.f;
             }
             // inter-chunk read: o[t][j] = sum_n (r_t W(t,-1))[n] S[n][j]; the state registers,
-            // rounded to fp16, are the B operand (k-slot order = the r tile's column permutation)
+            // rounded to fp16, are the A operand (k-slot order = the r tile's column permutation)
             if constexpr (!kStateOnly) {
                 half8 sh[2];
 #pragma unroll
@@ -888,13 +929,13 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
 #pragma unroll
                     for (int kk = 0; kk < 2; ++kk) {
                         const half8 rt = lds_read_h8(lds, kRT + (16 * tq + l16) * kRow + (32 * kk + 8 * g4) * 2);
-                        o[tq] = mfma(rt, sh[kk], o[tq]);
+                        o[tq] = mfma(sh[kk], rt, o[tq]);
                     }
                 }
             }
             if (a.decay_out) dtot *= *reinterpret_cast<const float*>(lds + kD + lane * 4);
             // state update: S = diag(W(32,-1)) S + (k W(32,i))^T V over the chunk's 32 tokens
-            vt = lds_read_tr8(lds, kVT + tr_lane + 32 * cw);
+            vt = lds_read_h8(lds, kVT + tile_t_off(16 * cw + l16, g4));
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) {
                 const float4 d = *reinterpret_cast<const float4*>(lds + kD + (16 * nb + 4 * g4) * 4);
@@ -902,7 +943,7 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
                 S[nb][1] *= d.y;
                 S[nb][2] *= d.z;
                 S[nb][3] *= d.w;
-                const half8 kt = lds_read_tr8(lds, kKT + tr_lane + 32 * nb);
+                const half8 kt = lds_read_h8(lds, kKT + tile_t_off(16 * nb + l16, g4));
                 S[nb] = mfma(kt, vt, S[nb]);
             }
             if (at.c == un.nchunks - 1) {
