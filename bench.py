@@ -6,7 +6,14 @@ synthetic Finch-1.6B-shaped inputs (B=8, T=4096, H=32, N=64, bf16 r/k/v/x, fp32 
 state, zero initial state, bf16 output and fp32 final state written).  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2..5] [--entry NAME]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2..5] [--entry NAME] [--preheat-ms MS]
+
+Before the W warm-up steps the same step is launched back to back for --preheat-ms milliseconds
+(default 300, untimed, reported as "preheat_ms"): an idle MI355X runs its first ~100 launches at
+low clocks (per-launch time falls from ~210 us to its sustained value), so without it a short
+run times the clock ramp, not the kernel.  The W warm-up steps and the K timed steps follow
+unchanged.  After the timed region the output and final state of a few (batch, head) units of
+the last timed step are compared with the fp64 oracle ("parity" in the JSON line).
 """
 import argparse
 import json
@@ -21,15 +28,64 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 MFMA
 
-# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each
-# scaled by the same counter's reading for a plain copy kernel); see profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE (KiB) x 2.0 (copy calibration) + WRITE_SIZE (KiB) x 1.0
-    "config2:wkv6_prefill_bf16": int(262260 * 1024 * 2.0 + 135168 * 1024 * 1.0),
-    "config2:wkv6_finch_c2_prefill_bf16": int(327806 * 1024 * 2.0 + 135168 * 1024 * 1.0),
-    "config2:wkv6_decode_bf16": int(270381 * 1024 * 2.0 + 528416 * 1024 * 1.0),
-    "config2:wkv6_key_compress_bf16": int(67636 * 1024 * 2.0 + 8192 * 1024 * 1.0),
+# HBM traffic per launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, each
+# scaled by the same counter's reading for a plain copy kernel of known size).  These are figures
+# from the named summaries under profiles/, not something this run measures: the JSON line carries
+# the file name next to the number, and null for workloads that were never profiled.
+# value = FETCH_SIZE (KiB) x 2.0 (copy calibration) + WRITE_SIZE (KiB) x 1.0
+PROFILED_TRAFFIC = {
+    ("config 2", "wkv6_prefill_bf16"): (int(262260 * 1024 * 2.0 + 135168 * 1024 * 1.0), "profiles/chunked_kernel_config2.md"),
+    ("config 2", "wkv6_finch_c2_prefill_bf16"): (int(327806 * 1024 * 2.0 + 135168 * 1024 * 1.0), "profiles/finch_c2_kernel_config2.md"),
+    ("decode-step B=1024", "wkv6_decode_bf16"): (int(270381 * 1024 * 2.0 + 528416 * 1024 * 1.0), "profiles/decode_step_B1024.md"),
+    ("key compression M=32768 D=2048", "wkv6_key_compress_bf16"): (int(67636 * 1024 * 2.0 + 8192 * 1024 * 1.0), "profiles/key_compress_config2_tokens.md"),
 }
+KERNEL_CHUNK = 32               # tokens per chunk of the chunked kernel (for the matrix-core flop count)
+
+
+def profiled_traffic(workload_key, entry):
+    value, source = PROFILED_TRAFFIC.get((workload_key, entry), (None, None))
+    return value, source
+
+
+def preheat(step, torch, ms):
+    """Launch `step` back to back for about `ms` milliseconds (untimed) so the timed region starts at
+    the chip's sustained clocks."""
+    if ms <= 0:
+        return 0
+    n = 0
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(50):
+            step()
+        torch.cuda.synchronize()
+        n += 50
+    return n
+
+
+def timed_region(step, steps, stream, torch):
+    """Exactly `steps` launches between one pair of HIP events recorded on the launch stream, bracketed
+    by synchronisations and the host clock.  Returns (average launch duration by the events in ms,
+    host-clock ms per step, per-launch durations of a second, untimed pass of at most 100 launches
+    with an event after every launch: a marker between two launches costs about 4 us, which is why
+    the timed region itself carries only the outer pair)."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = e0.elapsed_time(e1) / steps
+    n = min(steps, 100)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    evs[0].record(stream)
+    for i in range(n):
+        step()
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    return kernel_ms, wall * 1e3 / steps, [evs[i].elapsed_time(evs[i + 1]) for i in range(n)]
 
 
 def algorithmic_bytes(cfg, out_bytes, state_in, state_out=True, streams_in=4):
@@ -41,7 +97,7 @@ def algorithmic_bytes(cfg, out_bytes, state_in, state_out=True, streams_in=4):
     return cfg.token_heads * per_token_head + state * (int(state_in) + int(state_out))
 
 
-def algorithmic_flops(cfg, chunk=64):
+def algorithmic_flops(cfg, chunk=KERNEL_CHUNK):
     """Matrix-core flops of the chunked form per launch: 4*C*N + 4*N*N per token and head."""
     return cfg.token_heads * (4 * chunk * cfg.N + 4 * cfg.N * cfg.N)
 
@@ -76,13 +132,48 @@ def cpu_baseline(cfg, inp, finch_c2=False):
             "value_single_thread": cfg.T / dt1}
 
 
+def check_units(args, cfg, inp, out, s_out, finch_c2, decode, torch):
+    """What the last timed step wrote, for a handful of (batch, head) units, against the fp64 oracle:
+    max |gpu - oracle| / max |oracle| over those units, for the output and the final state."""
+    import numpy as np
+    from oracle import finch_c2_oracle, wkv6_oracle
+    if args.entry in ("wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16"):
+        return None                       # logits formed in the kernel: covered by tests/test_gpu_decay_lora.py
+    if decode:
+        return None                       # the state is updated in place step after step: tests/test_gpu_decode_append.py
+    B, H = cfg.B, cfg.H
+    units = sorted({(0, 0), (B - 1, H - 1), (B // 2, 3 % H), (B // 3, 11 % H), (B - 1, 19 % H), (0, H // 2)})
+    worst_o = worst_s = 0.0
+    for (b, h) in units:
+        sl = lambda a: np.ascontiguousarray(a[b:b + 1, :, h:h + 1])
+        s0 = None if inp["state_in"] is None else np.ascontiguousarray(inp["state_in"][b:b + 1, h:h + 1])
+        if finch_c2:
+            o_ref, s_ref = finch_c2_oracle(sl(inp["r"]), sl(inp["k"]), sl(inp["v"]), sl(inp["x"]), sl(inp["uprime"]), s0,
+                                           nthreads=1)
+        else:
+            o_ref, s_ref = wkv6_oracle(sl(inp["r"]), sl(inp["k"]), sl(inp["v"]), sl(inp["x"]), inp["u"][h:h + 1], s0,
+                                       nthreads=1)
+        got_o = out[b, :, h].float().cpu().numpy()
+        worst_o = max(worst_o, float(np.abs(got_o - o_ref[0, :, 0]).max() / np.abs(o_ref).max()))
+        got_s = s_out[b, h].cpu().numpy()
+        worst_s = max(worst_s, float(np.abs(got_s - s_ref[0, 0]).max() / np.abs(s_ref).max()))
+    out_is_bf16 = out.dtype == torch.bfloat16
+    return {"units_checked": len(units), "err_out": worst_o, "err_state": worst_s,
+            "tolerance_out": 2e-3 + (2.0 ** -8 if out_is_bf16 else 0.0), "tolerance_state": 2e-3,
+            "against": "fp64 oracle on the same inputs, per unit max-normalised",
+            "ok": bool(worst_o <= 2e-3 + (2.0 ** -8 if out_is_bf16 else 0.0) and worst_s <= 2e-3)}
+
+
 def bench_key_compress(args, torch, wkv):
     """The step after the path: c = x W^KD for the tokens of the chosen configuration (B*T tokens,
     D = H*N), x and W^KD resident in HBM, bf16 output."""
     from oracle import key_compress_oracle
     from paper_2407_12077_amd.workloads import CONFIGS, make_key_compress_inputs
     cfg = CONFIGS[args.config]
-    M, D = cfg.B * cfg.T, cfg.H * cfg.N
+    D = cfg.H * cfg.N
+    # at least 131072 tokens unless --tokens says otherwise: with config 2's own 32768 tokens x is
+    # 134 MB and partly served by the 256 MB last-level cache, which flatters the rate
+    M = args.tokens if args.tokens > 0 else max(cfg.B * cfg.T, 131072)
     C = D // 16
     x, w = make_key_compress_inputs(M, D)
     xd = torch.from_numpy(x).to(torch.bfloat16).cuda()
@@ -93,20 +184,12 @@ def bench_key_compress(args, torch, wkv):
     def step():
         wkv.wkv6_key_compress_bf16(M, D, xd, wd, c, wkv.WKV6_DTYPE_BF16, stream.cuda_stream)
 
+    preheat_launches = preheat(step, torch, args.preheat_ms)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    t0 = time.perf_counter()
-    evs[0].record(stream)
-    for i in range(args.steps):
-        step()
-        evs[i + 1].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
-    kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
-    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms, ms_per_step, per_launch_ms = timed_region(step, args.steps, stream, torch)
+    traffic, traffic_source = profiled_traffic(f"key compression M={M} D={D}", args.entry)
     abytes = M * D * 2 + D * C * 2 + M * C * 2
     aflops = 2 * M * D * C
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
@@ -115,16 +198,24 @@ def bench_key_compress(args, torch, wkv):
         "value": M / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 operands, f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"key compression of config {cfg.index}'s tokens: M={M} D={D}",
-                   "entry": args.entry, "global_batch": cfg.B, "seq_len": cfg.T},
+        "preheat_ms": args.preheat_ms, "preheat_launches": preheat_launches,
+        "config": {"workload": f"key compression at the width of config {cfg.index}: M={M} tokens, D={D}",
+                   "entry": args.entry, "tokens": M},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"config{args.config}:{args.entry}"),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms_avg": kernel_ms,
-                     "kernel_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
-                     "kernel_ms_min": min(per_launch_ms), "algorithmic_bytes": abytes,
+                     "per_launch_event_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
+                     "per_launch_event_ms_min": min(per_launch_ms), "algorithmic_bytes": abytes,
                      "mfma_frac": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
     }
+    # rows of the last timed launch against the oracle
+    rows = sorted({0, M - 1, *((i * 2654435761) % M for i in range(62))})
+    import numpy as np
+    got = c[rows].float().cpu().numpy()
+    ref = key_compress_oracle(x[rows], w)
+    result["parity"] = {"rows_checked": len(rows), "err": float(np.abs(got - ref).max() / np.abs(ref).max()),
+                        "tolerance": 2.0 ** -8, "against": "fp64 oracle, bf16 output"}
     if not args.no_cpu_baseline:
         cores = min(os.cpu_count() or 1, 16)
         nrows = min(M, 4096)
@@ -139,11 +230,8 @@ def bench_key_compress(args, torch, wkv):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # The chip raises its clocks over the first ~100 launches of a back-to-back sequence (per-launch
-    # time falls from ~210 us to ~145 us on config 2), so the defaults warm up past that ramp and
-    # time the sustained rate.
     ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=150)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--entry", default="wkv6_prefill_bf16",
                     choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent",
@@ -151,6 +239,9 @@ def main():
                              "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_moments",
                              "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16", "wkv6_decode_bf16", "wkv6_key_compress_bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--preheat-ms", type=float, default=300.0,
+                    help="untimed back-to-back launches of the step for this long before the warm-up steps")
+    ap.add_argument("--tokens", type=int, default=0, help="key compression only: number of tokens M")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 512 MiB device copy (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -252,21 +343,11 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    preheat_launches = preheat(step, torch, args.preheat_ms)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # per-launch durations with HIP events on the launch stream, inside the timed region
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    t0 = time.perf_counter()
-    evs[0].record(stream)
-    for i in range(args.steps):
-        step()
-        evs[i + 1].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    per_launch_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
-    kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
-    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms, ms_per_step, per_launch_ms = timed_region(step, args.steps, stream, torch)
 
     abytes = algorithmic_bytes(cfg, 4 if out_f32 else 2, s_in is not None, streams_in=5 if finch_c2 else 4)
     if args.entry in ("wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16"):
@@ -276,7 +357,8 @@ def main():
         abytes += B * T * H * 8 * 2 + B * T * 8      # partials written and read back once, two numbers per token
     aflops = algorithmic_flops(cfg)
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
-    key = f"config{args.config}:{args.entry}"
+    workload_key = f"decode-step B={B}" if decode else f"config {cfg.index}"
+    traffic, traffic_source = profiled_traffic(workload_key, args.entry)
     result = {
         "metric": "WKV6 prefill tokens/s per layer (H=%d,N=%d,bf16)" % (H, N),
         "value": B * T / (ms_per_step * 1e-3),
@@ -284,6 +366,8 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "preheat_ms": args.preheat_ms,
+        "preheat_launches": preheat_launches,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -296,12 +380,13 @@ def main():
                                f"{'nonzero' if s_in is not None else 'zero'} initial state",
                    "entry": args.entry, "segments": segments, "global_batch": B, "seq_len": T},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(key),
-                     "kernel_ms_avg": kernel_ms, "kernel_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
-                     "kernel_ms_min": min(per_launch_ms),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel_ms_avg": kernel_ms, "per_launch_event_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
+                     "per_launch_event_ms_min": min(per_launch_ms),
                      "algorithmic_bytes": abytes,
                      "mfma_frac": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
     }
+    result["parity"] = check_units(args, cfg, inp, out, s_out, finch_c2, decode, torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, finch_c2)
     print(json.dumps(result))

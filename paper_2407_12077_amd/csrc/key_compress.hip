@@ -264,14 +264,14 @@ hipError_t launch_key_compress(long long M, int D, const void* x, const void* w,
     const long long row_tiles = (M + kBM - 1) / kBM;
     const dim3 grid(static_cast<unsigned>((row_tiles + 7) / 8 * 8 * ((a.C + kBN - 1) / kBN)));
     hipError_t err;
+    struct TagF32 {};
+    struct TagBf16 {};
     if (out_f32) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void*>(&key_compress_kernel<true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kKcLds);
+        err = set_lds_limit_once<TagF32>(&key_compress_kernel<true>, kKcLds);
         if (err != hipSuccess) return err;
         hipLaunchKernelGGL(key_compress_kernel<true>, grid, dim3(kKcThreads), kKcLds, stream, a);
     } else {
-        err = hipFuncSetAttribute(reinterpret_cast<const void*>(&key_compress_kernel<false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kKcLds);
+        err = set_lds_limit_once<TagBf16>(&key_compress_kernel<false>, kKcLds);
         if (err != hipSuccess) return err;
         hipLaunchKernelGGL(key_compress_kernel<false>, grid, dim3(kKcThreads), kKcLds, stream, a);
     }

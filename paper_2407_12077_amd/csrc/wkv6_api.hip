@@ -303,7 +303,8 @@ extern "C" {
 int wkv6_split_segments(int B, int T, int H, int N) {
     if (N != wkv6::kHeadSize || B < 1 || T < 1 || H < 1) return 1;
     const long long units = static_cast<long long>(B) * H;
-    const int cus = 256;                         // workgroups resident at once (one per CU)
+    const int cus = 256;                         // workgroups resident at once on an MI355X (one per CU); a
+                                                 // pure function of the shape so that it needs no device
     if (units * 4 > cus * 3) return 1;           // already fills three quarters of the chip
     long long segs = cus / units;
     const long long by_len = T / 2048;           // keep segments long enough to amortise pass 1

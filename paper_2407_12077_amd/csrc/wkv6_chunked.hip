@@ -59,6 +59,7 @@
 // the operands of the consumers' MFMAs, so that a lane holds four consecutive value channels of
 // one token and stages them with one store.
 #include "wkv6_launch.h"
+#include "wkv6_windows.h"
 
 #include <type_traits>
 
@@ -73,7 +74,7 @@ typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kChunk = 32;                 // tokens per chunk
-constexpr int kProducerGroups = 3;         // 4 waves each
+constexpr int kProducerGroups = kWindowGroups;   // 4 waves each
 constexpr int kThreads = 64 * (4 * kProducerGroups + 4);
 constexpr int kRow = 160;                  // fp16 tile row stride in bytes (64 halfs + 16 pad)
 constexpr int kTile = kChunk * kRow;       // one [32 tokens][64 channels] tile
@@ -704,7 +705,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // reads before the barrier, and fills the gaps.  Measured against equal priorities: config 2
     // -3 %, config 5 -4 to -12 % depending on the box, fp32 output -8 %, nothing slower.
     const int total = un.count * un.nchunks;
-    const int nwin = (total + 6) / 3 * 3;
+    const int nwin = window_count(total);
     Cursor<kMulti> cur{0, 0}, ld{0, 0}, stc{0, pg - 2};      // chunk g, chunk g+6 (loads), chunk g-2 (stores)
     cur.advance(pg, un.nchunks);
     ld.advance(pg, un.nchunks);
@@ -753,12 +754,12 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     }
     int g = pg;
 #pragma clang loop unroll(disable)
-    for (; g + 5 < nwin; g += 6) {
+    for (; has_cycle_pair(g, nwin); g += 6) {       // same walk as producer_walk() in wkv6_windows.h
         cycle(g, raw_a);
         cycle(g + 3, raw_b);
         done += 6;
     }
-    if (g + 2 < nwin) {
+    if (has_cycle(g, nwin)) {
         cycle(g, raw_a);
         done += 3;
     }
@@ -819,7 +820,7 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
     half8 vt;           // V^T operand of that chunk: this lane's value channel, tokens 8*g4 .. +7
 
     const int total = un.count * un.nchunks;
-    const int nwin = (total + 6) / 3 * 3;
+    const int nwin = window_count(total);
 
     // Fused decay path.  This wave forms the decay logits of its 16 channels (16cw .. 16cw+15, as
     // key channels) for all 32 tokens of the chunk the producers digest in the next window:
@@ -1057,17 +1058,18 @@ __global__ __launch_bounds__(256) void combine_kernel(int H, int segs, const flo
     }
 }
 
-// Compute units of the MI355X: with more (batch, head) units than this, each workgroup takes
-// several of them back to back.
-constexpr int kComputeUnits = 256;
+template <int kMode, bool kC2, bool kMulti>
+struct ChunkedTag {};
 
 template <int kMode, bool kC2>
 hipError_t launch_mode(const Args& args, hipStream_t stream) {
     Args a = args;
     long long units = static_cast<long long>(a.B) * a.segs * a.H;
     a.unit_stride = 0;
-    if (a.segs == 1 && a.H <= kComputeUnits) {
-        const int per_round = a.H * (kComputeUnits / a.H);       // a multiple of H: the head stays fixed
+    // With more (batch, head) units than compute units each workgroup takes several of them back to back.
+    const int cus = compute_units();
+    if (a.segs == 1 && a.H <= cus) {
+        const int per_round = a.H * (cus / a.H);                 // a multiple of H: the head stays fixed
         if (units > per_round) {
             a.unit_stride = per_round;
             units = per_round;
@@ -1075,17 +1077,16 @@ hipError_t launch_mode(const Args& args, hipStream_t stream) {
     }
     const dim3 grid(static_cast<unsigned>(units));
     constexpr int lds_bytes = kMode >= 4 ? kLdsBytesLora : kLdsBytes;
-    auto go = [&](auto kernel) {
-        const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    auto go = [&](auto tag, auto kernel) {
+        const hipError_t err = set_lds_limit_once<decltype(tag)>(kernel, lds_bytes);
         if (err != hipSuccess) return err;
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, stream, a);
         return hipGetLastError();
     };
     if constexpr (kMode != 2) {
-        if (a.unit_stride > 0) return go(&chunked_kernel<kMode, kC2, true>);
+        if (a.unit_stride > 0) return go(ChunkedTag<kMode, kC2, true>{}, &chunked_kernel<kMode, kC2, true>);
     }
-    return go(&chunked_kernel<kMode, kC2, false>);
+    return go(ChunkedTag<kMode, kC2, false>{}, &chunked_kernel<kMode, kC2, false>);
 }
 
 }  // namespace

@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 namespace wkv6 {
 
 constexpr int kHeadSize = 64;   // N: the only head size the kernels are built for
@@ -71,6 +73,37 @@ hipError_t launch_key_compress(long long M, int D, const void* x, const void* w,
 // 1/sqrt(variance + eps) over all H*N channels: moments [B][H][T][2] -> mean_rstd [B][T][2].
 hipError_t launch_layernorm_finalize(int B, int T, int H, const float* moments, float eps, float* mean_rstd,
                                      hipStream_t stream);
+
+// Raises a kernel's dynamic LDS limit once per device and kernel instantiation (the attribute
+// belongs to the loaded function on a device, so it need not be set again at every launch, and must
+// not be set under stream capture: a process that captures should make its first call to an entry
+// point outside the capture).  `Tag` makes one flag set per kernel.
+template <typename Tag, typename Kernel>
+inline hipError_t set_lds_limit_once(Kernel kernel, int bytes) {
+    static std::atomic<unsigned long long> done{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    const unsigned long long bit = 1ull << dev;
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (err == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return err;
+}
+
+// Compute units of the current device (256 on an MI355X), read once per device; 256 if the
+// query fails.
+inline int compute_units() {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n <= 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
 
 // T == 0: state_out = state_in (or zero).
 hipError_t launch_state_passthrough(const Args& a, hipStream_t stream);
