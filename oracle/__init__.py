@@ -20,8 +20,12 @@ and never imports it.
 ``lora_numpy`` / ``decay_logits_numpy``
                   the low-rank operator lambda + tanh(x A) B and its last factor, the decay logits
                   from y = tanh(. A) (``decay_lora_numpy.py``).
+``lerp_numpy`` / ``token_shift_numpy`` / ``ddlerp_numpy`` / ``decay_lora_input_numpy``
+                  the operators in front of the decay path: token shift, ddlerp with its inner lora,
+                  and y = tanh(ddlerp_d(x_t, x_{t-1}) A_omega) (``ddlerp_numpy.py``).
 """
 from .cbuild import build_oracle, finch_c2_oracle, key_compress_oracle, wkv6_oracle  # noqa: F401
+from .ddlerp_numpy import decay_lora_input_numpy, ddlerp_numpy, lerp_numpy, token_shift_numpy  # noqa: F401
 from .decay_lora_numpy import decay_logits_numpy, lora_numpy  # noqa: F401
 from .layernorm_numpy import head_moments_numpy, layernorm_heads_numpy  # noqa: F401
 from .wkv6_numpy import finch_c2_numpy, wkv6_numpy  # noqa: F401
