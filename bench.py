@@ -164,6 +164,67 @@ def check_units(args, cfg, inp, out, s_out, finch_c2, decode, torch):
             "ok": bool(worst_o <= 2e-3 + (2.0 ** -8 if out_is_bf16 else 0.0) and worst_s <= 2e-3)}
 
 
+def bench_decay_front(args, torch, wkv):
+    """The operators in front of the decay path: y = tanh(ddlerp_d(x_t, x_{t-1}) A_omega) for the tokens of
+    the chosen configuration; x and the weights resident in HBM, bf16 output."""
+    import numpy as np
+    from oracle import decay_lora_input_numpy
+    from paper_2407_12077_amd.workloads import CONFIGS, make_decay_front_inputs
+    cfg = CONFIGS[args.config]
+    B, T, D = cfg.B, cfg.T, cfg.H * cfg.N
+    fi = make_decay_front_inputs(cfg)
+    dev = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(dt).cuda()
+    x, xp = dev(fi["x"], torch.bfloat16), dev(fi["x_prev"], torch.bfloat16)
+    mu, lam = dev(fi["mu_x"], torch.float32), dev(fi["lam_d"], torch.float32)
+    a_d, b_d, a_w = (dev(fi[n].T, torch.bfloat16) for n in ("A_d", "B_d", "A_omega"))
+    y = torch.empty((B, T, 64), dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        wkv.wkv6_decay_lora_input_bf16(B, T, D, 32, 64, x, xp, mu, lam, a_d, b_d, a_w, y, wkv.WKV6_DTYPE_BF16,
+                                       stream.cuda_stream)
+
+    preheat_launches = preheat(step, torch, args.preheat_ms)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    kernel_ms, ms_per_step, per_launch_ms = timed_region(step, args.steps, stream, torch)
+    M = B * T
+    abytes = M * D * 2 + M * 64 * 2 + B * D * 2 + 2 * D * 4 + (32 + 32 + 64) * D * 2
+    aflops = 2 * M * D * (32 + 32 + 64)
+    achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    result = {
+        "metric": "decay-path front tokens/s (D=%d -> 32 -> D -> 64, bf16)" % D,
+        "value": M / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "preheat_ms": args.preheat_ms, "preheat_launches": preheat_launches,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 tensors; f16 MFMA operands, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"decay-path front of config {cfg.index}: B={B} T={T} D={D}", "entry": args.entry,
+                   "global_batch": B, "seq_len": T},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "traffic_source": None,
+                     "kernel_ms_avg": kernel_ms,
+                     "per_launch_event_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
+                     "per_launch_event_ms_min": min(per_launch_ms), "algorithmic_bytes": abytes,
+                     "mfma_frac": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
+    }
+    nb, nt = 1, min(T, 512)
+    ref = decay_lora_input_numpy(fi["x"][:nb, :nt], fi["x_prev"][:nb], fi["mu_x"], fi["lam_d"], fi["A_d"], fi["B_d"],
+                                 fi["A_omega"])
+    got = y[:nb, :nt].float().cpu().numpy()
+    result["parity"] = {"tokens_checked": nb * nt, "err": float(np.abs(got - ref).max() / np.abs(ref).max()),
+                        "tolerance": 2e-3 + 2.0 ** -8, "against": "fp64 oracle, bf16 output"}
+    if not args.no_cpu_baseline:
+        nt = min(T, 4096)
+        t0 = time.perf_counter()
+        decay_lora_input_numpy(fi["x"][:1, :nt], fi["x_prev"][:1], fi["mu_x"], fi["lam_d"], fi["A_d"], fi["B_d"],
+                               fi["A_omega"])
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": nt / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"first {nt} tokens of the first sequence, fp64 NumPy, {dt:.2f} s"}
+    print(json.dumps(result))
+
+
 def bench_key_compress(args, torch, wkv):
     """The step after the path: c = x W^KD for the tokens of the chosen configuration (B*T tokens,
     D = H*N), x and W^KD resident in HBM, bf16 output."""
@@ -237,7 +298,8 @@ def main():
                     choices=["wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_recurrent",
                              "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
                              "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_moments",
-                             "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16", "wkv6_decode_bf16", "wkv6_key_compress_bf16"])
+                             "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16", "wkv6_decode_bf16", "wkv6_key_compress_bf16",
+                             "wkv6_decay_lora_input_bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--preheat-ms", type=float, default=300.0,
                     help="untimed back-to-back launches of the step for this long before the warm-up steps")
@@ -260,6 +322,8 @@ def main():
     wkv.load()                                   # fails loudly if the HIP library is missing
     if args.entry == "wkv6_key_compress_bf16":
         return bench_key_compress(args, torch, wkv)
+    if args.entry == "wkv6_decay_lora_input_bf16":
+        return bench_decay_front(args, torch, wkv)
     cfg = CONFIGS[args.config]
     decode = args.entry == "wkv6_decode_bf16"
     if decode:

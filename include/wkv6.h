@@ -253,6 +253,45 @@ int wkv6_finch_c2_prefill_lora_bf16(int B, int T, int H, int N, int R,
                                     void *out, float *moments, float *state_out, void *stream);
 
 /*
+ * The operators in front of that call (paper: Method, "Finch-C2 Time Mixing": lerp(a, b, t) =
+ * a + (b - a) t, lora(x) = lambda + tanh(x A) B, ddlerp(a, b) = a + (b - a) lora(a + (b - a) mu_x), and
+ * d_t = lora_omega(ddlerp_d(x_t, x_{t-1}))): from the time-mix input x to the low-rank activations
+ *
+ *     z_t = x_t + (x_{t-1} - x_t) * (lambda_d + tanh((x_t + (x_{t-1} - x_t) * mu_x) A_d) B_d)
+ *     y_t = tanh(z_t A_omega)
+ *
+ * that wkv6_finch_c2_prefill_lora_bf16 / wkv6_prefill_lora_bf16 take, so the decay path runs from the
+ * layer input to the decay inside this library and neither z nor the logits exist in HBM.  One
+ * kernel, bound by the one HBM read of x (algorithmic bytes 2 B T D in + 2 B T R out + weights).
+ *
+ *   B, T     batch, tokens per sequence (B*T = 0 is a no-op)
+ *   D        model width H*N, a multiple of 128 up to 65536
+ *   R_d, R   inner rank of ddlerp_d's lora and rank of lora_omega: must be 32 and 64 (Finch's sizes;
+ *            WKV6_ERR_UNSUPPORTED otherwise)
+ *   x        [B][T][D]  bf16  input of the time-mix block
+ *   x_prev   [B][D]     bf16  the token before each sequence's first one (a carried row when a context
+ *                             is processed in pieces), or NULL: nothing precedes it and x_{-1} = 0.
+ *                             The paper writes x_{t-1} without saying what precedes t = 0; zero is what
+ *                             Finch, from which the operators are taken, shifts in.
+ *   mu_x     [D]        fp32
+ *   lambda_d [D]        fp32
+ *   a_d      [R_d][D]   bf16  A_d stored column by column (row i is column i of the paper's D x R_d
+ *                             matrix): the contraction index must be contiguous for the matrix cores
+ *   b_d      [D][R_d]   bf16  B_d stored column by column (row c is column c of the paper's R_d x D)
+ *   a_omega  [R][D]     bf16  A_omega stored column by column
+ *   y        [B][T][R]  bf16 or fp32 per out_dtype (a wkv6_dtype)
+ * All device pointers, 16-byte aligned.  Arithmetic: interpolations in fp32, matrix-core operands
+ * fp16 (q, p, z and the weights; 11 significant bits), fp32 accumulation, tanh from one
+ * exponential and one reciprocal in fp32; |x| and the weights must stay inside the fp16 range.
+ * Enqueues one kernel on `stream`; allocates nothing; errors as for the other entry points.
+ */
+int wkv6_decay_lora_input_bf16(int B, int T, int D, int R_d, int R,
+                               const void *x, const void *x_prev,
+                               const float *mu_x, const float *lambda_d,
+                               const void *a_d, const void *b_d, const void *a_omega,
+                               void *y, int out_dtype, void *stream);
+
+/*
  * The Finch form (bonus u, plain key) with the same fusion: Finch's own decay is the same
  * low-rank path (the paper takes the operators from Finch), so a Finch layer can hand over
  * y, lambda and b_omega instead of x as well.  Arguments as for wkv6_prefill_bf16 with

@@ -5,7 +5,7 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libwkv6.so")
-SOURCES = ["wkv6_api.hip", "wkv6_recurrent.hip", "wkv6_chunked.hip", "key_compress.hip", "layernorm_finalize.hip"]
+SOURCES = ["wkv6_api.hip", "wkv6_recurrent.hip", "wkv6_chunked.hip", "key_compress.hip", "layernorm_finalize.hip", "decay_input.hip"]
 # packed-fp32 VALU forms are switched off on purpose for the whole library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -256,6 +256,24 @@ int wkv6_key_compress_bf16(long long M, int D, const void* x, const void* w_kd, 
     return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
 }
 
+int wkv6_decay_lora_input_bf16(int B, int T, int D, int R_d, int R, const void* x, const void* x_prev,
+                               const float* mu_x, const float* lambda_d, const void* a_d, const void* b_d,
+                               const void* a_omega, void* y, int out_dtype, void* stream) {
+    if (out_dtype != WKV6_DTYPE_BF16 && out_dtype != WKV6_DTYPE_F32) return WKV6_ERR_UNSUPPORTED;
+    if (R_d != 32 || R != wkv6::kLoraRank) return WKV6_ERR_UNSUPPORTED;
+    if (D < 128 || D % 128 != 0 || D > 65536) return WKV6_ERR_UNSUPPORTED;
+    if (B < 0 || T < 0) return WKV6_ERR_SHAPE;
+    if (B == 0 || T == 0) return WKV6_OK;
+    if (static_cast<long long>(B) * ((T + 127) / 128) > 0x7fffffffLL) return WKV6_ERR_SHAPE;  // grid size
+    if (!x || !mu_x || !lambda_d || !a_d || !b_d || !a_omega || !y) return WKV6_ERR_NULL;
+    if (misaligned(x) || misaligned(x_prev) || misaligned(mu_x) || misaligned(lambda_d) || misaligned(a_d) ||
+        misaligned(b_d) || misaligned(a_omega) || misaligned(y))
+        return WKV6_ERR_ALIGN;
+    const hipError_t err = wkv6::launch_decay_input(B, T, D, x, x_prev, mu_x, lambda_d, a_d, b_d, a_omega, y,
+                                                    out_dtype == WKV6_DTYPE_F32, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
+}
+
 const char* wkv6_status_string(int status) {
     switch (status) {
         case WKV6_OK: return "ok";

@@ -74,6 +74,13 @@ hipError_t launch_key_compress(long long M, int D, const void* x, const void* w,
 hipError_t launch_layernorm_finalize(int B, int T, int H, const float* moments, float eps, float* mean_rstd,
                                      hipStream_t stream);
 
+// Front of the decay path: y = tanh(ddlerp_d(x_t, x_{t-1}) A_omega), x [B][T][D] bf16, x_prev [B][D] bf16 or
+// nullptr, mu_x and lambda_d [D] fp32, a_d [32][D], b_d [D][32], a_omega [64][D] bf16, y [B][T][64] bf16
+// or fp32.  D must be a multiple of 128.
+hipError_t launch_decay_input(int B, int T, int D, const void* x, const void* x_prev, const float* mu_x,
+                              const float* lambda_d, const void* a_d, const void* b_d, const void* a_omega, void* y,
+                              bool out_f32, hipStream_t stream);
+
 // Raises a kernel's dynamic LDS limit once per device and kernel instantiation (the attribute
 // belongs to the loaded function on a device, so it need not be set again at every launch, and must
 // not be set under stream capture: a process that captures should make its first call to an entry

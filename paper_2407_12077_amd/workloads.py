@@ -148,6 +148,30 @@ def make_decay_lora_inputs(cfg, seed=None, rank=64):
     return {"y": round_to_bf16(y), "lam": lam, "b_omega": round_to_bf16(b_omega)}
 
 
+def make_decay_front_inputs(cfg, seed=None, inner_rank=32, rank=64):
+    """Inputs of the operators in front of the decay path for ``cfg`` (D = H*N): the time-mix input
+    x [B, T, D] ~ N(0, 1) (a LayerNorm output stands behind it in the model), the row x_prev [B, D]
+    before each sequence, the interpolation weights mu_x ~ U(0, 1) and lam_d ~ U(0, 1) (both are
+    per-channel mixing ratios between a token and its predecessor), and the three low-rank factors in
+    the paper's orientation: A_d [D, inner_rank] ~ N(0, 1/D) (unit-scale pre-activations),
+    B_d [inner_rank, D] ~ N(0, 0.1^2), A_omega [D, rank] ~ N(0, 1/D).  x, x_prev and the matrices are
+    rounded to bf16; everything is returned as float32 arrays.  Own generator, ``PCG64(seed + 3000)``."""
+    if seed is None:
+        seed = BASE_SEED + cfg.index
+    rng = np.random.Generator(np.random.PCG64(seed + 3000))
+    D = cfg.H * cfg.N
+    x = rng.standard_normal((cfg.B, cfg.T, D), dtype=np.float32)
+    x_prev = rng.standard_normal((cfg.B, D), dtype=np.float32)
+    mu_x = rng.random(D, dtype=np.float32)
+    lam_d = rng.random(D, dtype=np.float32)
+    inv = np.float32(1.0 / np.sqrt(D))
+    A_d = rng.standard_normal((D, inner_rank), dtype=np.float32) * inv
+    B_d = rng.standard_normal((inner_rank, D), dtype=np.float32) * np.float32(0.1)
+    A_omega = rng.standard_normal((D, rank), dtype=np.float32) * inv
+    return {"x": round_to_bf16(x), "x_prev": round_to_bf16(x_prev), "mu_x": mu_x, "lam_d": lam_d,
+            "A_d": round_to_bf16(A_d), "B_d": round_to_bf16(B_d), "A_omega": round_to_bf16(A_omega)}
+
+
 def make_key_compress_inputs(M, D, seed=BASE_SEED + 100):
     """Inputs of the GOLD key compression for M tokens of a model of width D: hidden states
     x [M, D] ~ N(0, 1) (a residual-stream activation stands in for the last Finch-C2 layer's

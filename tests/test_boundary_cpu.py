@@ -171,6 +171,30 @@ def test_fused_decay_path_validation():
     assert f(0, 8, 2, 64, 64, *([None] * 12)) == 0
 
 
+def test_decay_front_validation_and_recipe():
+    f = _raw("wkv6_decay_lora_input_bf16")
+    ok = (A, None, A, A, A, A, A, A, 0, None)     # x x_prev mu_x lambda_d a_d b_d a_omega y out_dtype stream
+    assert f(1, 8, 2048, 16, 64, *ok) == 3                                        # inner rank
+    assert f(1, 8, 2048, 32, 32, *ok) == 3                                        # outer rank
+    assert f(1, 8, 2000, 32, 64, *ok) == 3                                        # width not a multiple of 128
+    assert f(1, 8, 2048, 32, 64, A, None, A, A, A, A, A, A, 5, None) == 3          # dtype code
+    assert f(-1, 8, 2048, 32, 64, *ok) == 2
+    assert f(1, 8, 2048, 32, 64, None, None, A, A, A, A, A, A, 0, None) == 1       # x
+    assert f(1, 8, 2048, 32, 64, A, None, A, A, A, None, A, A, 0, None) == 1       # b_d
+    assert f(1, 8, 2048, 32, 64, A, P(0x1008), A, A, A, A, A, A, 0, None) == 5     # x_prev alignment
+    assert f(1, 0, 2048, 32, 64, *([None] * 8), 0, None) == 0
+    from paper_2407_12077_amd.workloads import CONFIGS, make_decay_front_inputs, round_to_bf16, scaled
+    cfg = scaled(CONFIGS[2], B=2, T=9, H=2)
+    a, b = make_decay_front_inputs(cfg), make_decay_front_inputs(cfg)
+    assert a["x"].shape == (2, 9, 128) and a["x_prev"].shape == (2, 128) and a["A_d"].shape == (128, 32)
+    assert a["B_d"].shape == (32, 128) and a["A_omega"].shape == (128, 64) and a["mu_x"].shape == (128,)
+    for k in a:
+        assert a[k].dtype == np.float32 and np.array_equal(a[k], b[k])
+    for k in ("x", "x_prev", "A_d", "B_d", "A_omega"):
+        assert np.array_equal(a[k], round_to_bf16(a[k]))
+    assert 0 <= a["mu_x"].min() and a["mu_x"].max() <= 1 and 0 <= a["lam_d"].min() and a["lam_d"].max() <= 1
+
+
 def test_decay_lora_workload_recipe():
     from paper_2407_12077_amd.workloads import CONFIGS, make_decay_lora_inputs, round_to_bf16, scaled
     cfg = scaled(CONFIGS[2], B=2, T=50, H=3)
