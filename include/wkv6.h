@@ -228,6 +228,26 @@ int wkv6_layernorm_finalize(int B, int T, int H, int N, const float *moments, fl
                             float *mean_rstd, void *stream);
 
 /*
+ * Applies those statistics (paper: Method, "Finch-C2 Time Mixing", output equation: the LayerNorm over
+ * the concatenated heads in front of W^O):
+ *
+ *     y[b][t][c] = (o[b][t][c] - mean[b][t]) * rstd[b][t] * gamma[c] + beta[c],      c = h*N + n
+ *
+ *   o          [B][T][H][N]  bf16  read-outs as written by the prefill entry points
+ *   mean_rstd  [B][T][2]     fp32  from wkv6_layernorm_finalize
+ *   gamma,beta [H*N]         fp32
+ *   y          [B][T][H*N]   bf16 or fp32 per out_dtype (may equal o for bf16: every element is read before
+ *                                  it is written, by the same thread)
+ * all device pointers, 16-byte aligned.  This is the plain form, one streaming pass over o (read once,
+ * written once), for callers whose projection GEMM cannot take the row scaling and rank-one correction
+ * described above in its epilogue; with such a GEMM it is not needed.  The statistics are those of the
+ * fp32 read-outs before their rounding to bf16, the values normalised are the rounded ones: the result
+ * differs from a LayerNorm of the rounded values by at most the rounding itself.
+ */
+int wkv6_layernorm_apply_bf16(int B, int T, int H, int N, const void *o, const float *mean_rstd,
+                              const float *gamma, const float *beta, void *y, int out_dtype, void *stream);
+
+/*
  * Finch-C2 prefill with the last factor of the decay path fused in (paper: Method, "Finch-C2
  * Time Mixing": lora(x) = lambda + tanh(x A) B and d_t = lora_omega(ddlerp_d(x_t, x_{t-1})),
  * w_t = exp(-exp(d_t))).  Instead of the decay logits x [B][T][H][N] the call takes the low-rank

@@ -21,7 +21,7 @@ EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_s
            "wkv6_split_workspace_bytes", "wkv6_split_segments", "wkv6_finch_c2_prefill_bf16",
            "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_strided",
            "wkv6_finch_c2_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16_moments",
-           "wkv6_layernorm_finalize", "wkv6_decay_lora_input_bf16", "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16",
+           "wkv6_layernorm_finalize", "wkv6_layernorm_apply_bf16", "wkv6_decay_lora_input_bf16", "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16",
            "wkv6_decode_bf16", "wkv6_finch_c2_decode_bf16", "wkv6_append_bf16",
            "wkv6_finch_c2_append_bf16", "wkv6_key_compress_bf16", "wkv6_status_string", "wkv6_version")
 
@@ -67,6 +67,8 @@ def load():
         lib.wkv6_prefill_lora_bf16.argtypes = [i, i, i, i, i] + [vp] * 11
         lib.wkv6_decay_lora_input_bf16.restype = i
         lib.wkv6_decay_lora_input_bf16.argtypes = [i, i, i, i, i] + [vp] * 8 + [i, vp]
+        lib.wkv6_layernorm_apply_bf16.restype = i
+        lib.wkv6_layernorm_apply_bf16.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, i, vp]
         lib.wkv6_layernorm_finalize.restype = i
         lib.wkv6_layernorm_finalize.argtypes = [i, i, i, i, vp, ctypes.c_float, vp, vp]
         lib.wkv6_key_compress_bf16.restype = i
@@ -203,6 +205,11 @@ def wkv6_decay_lora_input_bf16(B, T, D, R_d, R, x, x_prev, mu_x, lambda_d, a_d, 
     _check(load().wkv6_decay_lora_input_bf16(B, T, D, R_d, R, _ptr(x), _ptr(x_prev), _ptr(mu_x), _ptr(lambda_d),
                                              _ptr(a_d), _ptr(b_d), _ptr(a_omega), _ptr(y), int(out_dtype),
                                              _stream(stream)))
+
+
+def wkv6_layernorm_apply_bf16(B, T, H, N, o, mean_rstd, gamma, beta, y, out_dtype, stream=None):
+    _check(load().wkv6_layernorm_apply_bf16(B, T, H, N, _ptr(o), _ptr(mean_rstd), _ptr(gamma), _ptr(beta), _ptr(y),
+                                            int(out_dtype), _stream(stream)))
 
 
 def wkv6_layernorm_finalize(B, T, H, N, moments, eps, mean_rstd, stream=None):

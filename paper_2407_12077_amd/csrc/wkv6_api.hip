@@ -199,6 +199,22 @@ int wkv6_layernorm_finalize(int B, int T, int H, int N, const float* moments, fl
     return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
 }
 
+int wkv6_layernorm_apply_bf16(int B, int T, int H, int N, const void* o, const float* mean_rstd, const float* gamma,
+                              const float* beta, void* y, int out_dtype, void* stream) {
+    if (out_dtype != WKV6_DTYPE_BF16 && out_dtype != WKV6_DTYPE_F32) return WKV6_ERR_UNSUPPORTED;
+    if (N != wkv6::kHeadSize) return WKV6_ERR_UNSUPPORTED;
+    if (B < 0 || T < 0 || H < 1 || H > 262144) return WKV6_ERR_SHAPE;
+    if (B == 0 || T == 0) return WKV6_OK;
+    const long long tokens = static_cast<long long>(B) * T;
+    if ((tokens * (H * N / 8) + 255) / 256 > 0x7fffffffLL) return WKV6_ERR_SHAPE;               // grid size
+    if (!o || !mean_rstd || !gamma || !beta || !y) return WKV6_ERR_NULL;
+    if (misaligned(o) || misaligned(mean_rstd) || misaligned(gamma) || misaligned(beta) || misaligned(y))
+        return WKV6_ERR_ALIGN;
+    const hipError_t err = wkv6::launch_layernorm_apply(tokens, H * N, o, mean_rstd, gamma, beta, y,
+                                                        out_dtype == WKV6_DTYPE_F32, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
+}
+
 int wkv6_append_bf16(int B, int T, int H, int N, const void* r, const void* k, const void* v,
                      const void* x, const float* u, const float* state_in, void* out,
                      float* state_out, void* stream) {

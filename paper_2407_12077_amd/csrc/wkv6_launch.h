@@ -74,6 +74,11 @@ hipError_t launch_key_compress(long long M, int D, const void* x, const void* w,
 hipError_t launch_layernorm_finalize(int B, int T, int H, const float* moments, float eps, float* mean_rstd,
                                      hipStream_t stream);
 
+// Applies the token statistics: y = (o - mean) * rstd * gamma + beta; o [tokens][D] bf16, mean_rstd
+// [tokens][2], gamma and beta [D] fp32, y [tokens][D] bf16 or fp32.  D must be a multiple of 8.
+hipError_t launch_layernorm_apply(long long tokens, int D, const void* o, const float* mean_rstd, const float* gamma,
+                                  const float* beta, void* y, bool out_f32, hipStream_t stream);
+
 // Front of the decay path: y = tanh(ddlerp_d(x_t, x_{t-1}) A_omega), x [B][T][D] bf16, x_prev [B][D] bf16 or
 // nullptr, mu_x and lambda_d [D] fp32, a_d [32][D], b_d [D][32], a_omega [64][D] bf16, y [B][T][64] bf16
 // or fp32.  D must be a multiple of 128.

@@ -157,6 +157,16 @@ def test_layernorm_moments_validation():
     assert g(1, 0, 2, 64, None, ctypes.c_float(1e-5), None, None) == 0
 
 
+def test_layernorm_apply_validation():
+    f = _raw("wkv6_layernorm_apply_bf16")
+    assert f(1, 8, 2, 32, A, A, A, A, A, 0, None) == 3
+    assert f(1, 8, 2, 64, A, A, A, A, A, 4, None) == 3
+    assert f(1, -1, 2, 64, A, A, A, A, A, 0, None) == 2
+    assert f(1, 8, 2, 64, A, A, None, A, A, 0, None) == 1
+    assert f(1, 8, 2, 64, A, P(0x1004), A, A, A, 0, None) == 5
+    assert f(0, 8, 2, 64, None, None, None, None, None, 0, None) == 0
+
+
 def test_fused_decay_path_validation():
     f = _raw("wkv6_finch_c2_prefill_lora_bf16")
     ok = (A, A, A, A, A, A, A, None, A, None, A, None)    # r kbar v y lambda b_omega uprime state_in out moments state_out stream

@@ -184,3 +184,64 @@ def test_validation(gpu_device):
     wkv.wkv6_layernorm_finalize(B, 0, H, N, None, EPS, None)   # nothing to do
     wkv.wkv6_finch_c2_prefill_bf16_moments(B, 0, H, N, None, None, None, None, None, None, None, None, None)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ the statistics applied on the GPU
+def run_applied(inp, gamma, beta, out_dtype, eps=EPS, in_place=False):
+    """prefill with partial moments -> fold -> wkv6_layernorm_apply_bf16, all on the GPU."""
+    B, T, H, N = inp["r"].shape
+    r, k, v, x, up = (to_dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "x", "uprime"))
+    s_in = to_dev(inp.get("state_in"), torch.float32)
+    out = torch.full((B, T, H, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    mom = torch.full((B, H, T, 2), float("nan"), dtype=torch.float32, device="cuda")
+    mr = torch.full((B, T, 2), float("nan"), dtype=torch.float32, device="cuda")
+    g, bt = to_dev(gamma, torch.float32), to_dev(beta, torch.float32)
+    y = out.view(B, T, H * N) if in_place else torch.full((B, T, H * N), float("nan"), dtype=out_dtype, device="cuda")
+    wkv.wkv6_finch_c2_prefill_bf16_moments(B, T, H, N, r, k, v, x, up, s_in, out, mom, None)
+    wkv.wkv6_layernorm_finalize(B, T, H, N, mom, eps, mr)
+    code = wkv.WKV6_DTYPE_F32 if out_dtype == torch.float32 else wkv.WKV6_DTYPE_BF16
+    wkv.wkv6_layernorm_apply_bf16(B, T, H, N, out, mr, g, bt, y, code)
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy().astype(np.float64).reshape(B, T, H, N)
+
+
+@pytest.mark.parametrize("dims", [dict(B=2, T=333, H=4), dict(B=1, T=70, H=32), dict(B=3, T=1, H=2), dict(B=1, T=1000, H=12)])
+def test_layernorm_applied_end_to_end(gpu_device, dims):
+    """From r, kbar, v, x, u' to LayerNorm(concat(heads)) with gain and offset, against the chained
+    oracles finch_c2_oracle -> layernorm_heads_numpy.  The read-outs pass through bf16 between the two
+    GPU kernels (that is the interface tensor), so the bar is the output's own (2e-3 + 2^-8), taken
+    relative to the largest normalised value; the bf16 result carries one more rounding."""
+    inp = inputs(scaled(CONFIGS[2], **dims), seed=31)
+    B, T, H, N = inp["r"].shape
+    rng = np.random.default_rng(32)
+    gamma = (1.0 + 0.3 * rng.standard_normal(H * N)).astype(np.float32)
+    beta = (0.2 * rng.standard_normal(H * N)).astype(np.float32)
+    o_ref, _ = finch_c2_oracle(inp["r"], inp["k"], inp["v"], inp["x"], inp["uprime"], None)
+    y_ref, _, _ = layernorm_heads_numpy(o_ref, gamma, beta, EPS)
+    y32 = run_applied(inp, gamma, beta, torch.float32)
+    e32 = max_norm_err(y32, y_ref)
+    y16 = run_applied(inp, gamma, beta, torch.bfloat16)
+    e16 = max_norm_err(y16, y_ref)
+    print(f"applied layernorm {dims}: fp32 out err={e32:.3e}, bf16 out err={e16:.3e}", flush=True)
+    assert e32 <= TOL_BF16 + BF16_OUT_ROUNDING and e16 <= TOL_BF16 + 2 * BF16_OUT_ROUNDING
+    assert np.array_equal(y16, round_to_bf16(y32.astype(np.float32)).astype(np.float64))
+    # in place over the read-outs (bf16)
+    assert np.array_equal(run_applied(inp, gamma, beta, torch.bfloat16, in_place=True), y16)
+    # the normalised rows have the statistics a LayerNorm promises (gain 1, offset 0)
+    y_plain = run_applied(inp, np.ones(H * N, np.float32), np.zeros(H * N, np.float32), torch.float32)
+    flat = y_plain.reshape(B, T, H * N)
+    assert np.abs(flat.mean(axis=2)).max() <= 5e-3 and np.abs(flat.var(axis=2) - 1.0).max() <= 2e-2
+
+
+def test_layernorm_apply_validation(gpu_device):
+    o = torch.zeros((1, 8, 2, 64), dtype=torch.bfloat16, device="cuda")
+    mr = torch.zeros((1, 8, 2), dtype=torch.float32, device="cuda")
+    g = torch.ones(128, dtype=torch.float32, device="cuda")
+    y = torch.zeros((1, 8, 128), dtype=torch.bfloat16, device="cuda")
+    wkv.wkv6_layernorm_apply_bf16(1, 8, 2, 64, o, mr, g, g, y, wkv.WKV6_DTYPE_BF16)
+    wkv.wkv6_layernorm_apply_bf16(0, 8, 2, 64, None, None, None, None, None, wkv.WKV6_DTYPE_BF16)
+    for args, status in [((1, 8, 2, 32, o, mr, g, g, y, 0), 3), ((1, 8, 2, 64, o, mr, g, g, y, 7), 3),
+                         ((1, 8, 0, 64, o, mr, g, g, y, 0), 2), ((1, 8, 2, 64, o, None, g, g, y, 0), 1)]:
+        with pytest.raises(wkv.Wkv6Error) as e:
+            wkv.wkv6_layernorm_apply_bf16(*args)
+        assert e.value.status == status
