@@ -226,14 +226,20 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const char* base, l
 
 // A chunk's loads are issued in two halves (x and r; k and v) so that two different phases can
 // share the cost of issuing them.
-template <bool kSkipR, bool kSkipX>
+// kPolicy: the cache policy of the loads.  Every mode streams (kStreamOnce), the state-only pass of the
+// token split included: running that split block by block with cached loads in its first pass, so that
+// the second read of k, v, x could come from the last-level cache, was measured and dropped (config 3:
+// 0.91 ms unblocked with cached first-pass loads, 0.90 to 1.10 ms in 4 to 16 blocks, against 0.78 ms
+// with streaming loads and one block; the byte counters of the L2, which cannot tell that cache from
+// HBM, did not move).
+template <bool kSkipR, bool kSkipX, int kPolicy>
 __device__ __forceinline__ void load_rows_xr(Raw& d, const Streams& st, long long unit_bytes, int t0,
                                              const int (&voff)[4]) {
     const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
     if constexpr (!kSkipX) {
         const __amdgpu_buffer_rsrc_t rx = chunk_rsrc(st.x + unit_bytes, off, st.span_bytes);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, kStreamOnce);
+        for (int s = 0; s < 4; ++s) d.x[s] = __builtin_amdgcn_raw_buffer_load_b32(rx, voff[s], 0, kPolicy);
     } else {
 #pragma unroll
         for (int s = 0; s < 4; ++s) d.x[s] = 0u;
@@ -241,13 +247,14 @@ __device__ __forceinline__ void load_rows_xr(Raw& d, const Streams& st, long lon
     if constexpr (!kSkipR) {
         const __amdgpu_buffer_rsrc_t rr = chunk_rsrc(st.r + unit_bytes, off, st.span_bytes);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, kStreamOnce);
+        for (int s = 0; s < 4; ++s) d.r[s] = __builtin_amdgcn_raw_buffer_load_b32(rr, voff[s], 0, kPolicy);
     } else {
 #pragma unroll
         for (int s = 0; s < 4; ++s) d.r[s] = 0u;
     }
 }
 
+template <int kPolicy>
 __device__ __forceinline__ void load_rows_kv(Raw& d, const Streams& st, long long unit_bytes, int t0,
                                              const int (&voff)[4]) {
     const long long off = static_cast<long long>(t0) * st.row_bytes;       // uniform
@@ -255,8 +262,8 @@ __device__ __forceinline__ void load_rows_kv(Raw& d, const Streams& st, long lon
     const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(st.v + unit_bytes, off, st.span_bytes);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-        d.k[s] = __builtin_amdgcn_raw_buffer_load_b32(rk, voff[s], 0, kStreamOnce);
-        d.v[s] = __builtin_amdgcn_raw_buffer_load_b32(rv, voff[s], 0, kStreamOnce);
+        d.k[s] = __builtin_amdgcn_raw_buffer_load_b32(rk, voff[s], 0, kPolicy);
+        d.v[s] = __builtin_amdgcn_raw_buffer_load_b32(rv, voff[s], 0, kPolicy);
     }
 }
 
@@ -712,11 +719,11 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     stc.advance(0, un.nchunks);
     auto fetch_xr = [&](Raw& buf, const Cursor<kMulti>& at) {
         const bool live = at.live(un);                // uniform; dead: offset past the span = empty descriptor
-        load_rows_xr<kStateOnly, kLora>(buf, st, live ? at.unit_elems(un) * 2 : 0, live ? at.c * kChunk : T + kChunk, voff);
+        load_rows_xr<kStateOnly, kLora, kStreamOnce>(buf, st, live ? at.unit_elems(un) * 2 : 0, live ? at.c * kChunk : T + kChunk, voff);
     };
     auto fetch_kv = [&](Raw& buf, const Cursor<kMulti>& at) {
         const bool live = at.live(un);
-        load_rows_kv(buf, st, live ? at.unit_elems(un) * 2 : 0, live ? at.c * kChunk : T + kChunk, voff);
+        load_rows_kv<kStreamOnce>(buf, st, live ? at.unit_elems(un) * 2 : 0, live ? at.c * kChunk : T + kChunk, voff);
     };
     // one chunk of this group through its three windows; `buf` holds its raw inputs and is
     // refilled with the group's chunk after next (six chunks ahead) right after the digest
@@ -1068,7 +1075,7 @@ hipError_t launch_mode(const Args& args, hipStream_t stream) {
     a.unit_stride = 0;
     // With more (batch, head) units than compute units each workgroup takes several of them back to back.
     const int cus = compute_units();
-    if (a.segs == 1 && a.H <= cus) {
+    if (kMode != 2 && a.segs == 1 && a.H <= cus) {
         const int per_round = a.H * (cus / a.H);                 // a multiple of H: the head stays fixed
         if (units > per_round) {
             a.unit_stride = per_round;
