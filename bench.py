@@ -34,9 +34,10 @@ MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 MFMA
 # the file name next to the number, and null for workloads that were never profiled.
 # value = FETCH_SIZE (KiB) x 2.0 (copy calibration) + WRITE_SIZE (KiB) x 1.0
 PROFILED_TRAFFIC = {
-    ("config 2", "wkv6_prefill_bf16"): (int(262260 * 1024 * 2.0 + 135168 * 1024 * 1.0), "profiles/chunked_kernel_config2.md"),
+    ("config 2", "wkv6_prefill_bf16"): (int(262300 * 1024 * 2.0 + 135200 * 1024 * 1.0), "profiles/chunked_kernel_config2.md"),
     ("config 2", "wkv6_finch_c2_prefill_bf16"): (int(327806 * 1024 * 2.0 + 135168 * 1024 * 1.0), "profiles/finch_c2_kernel_config2.md"),
     ("decode-step B=1024", "wkv6_decode_bf16"): (int(270381 * 1024 * 2.0 + 528416 * 1024 * 1.0), "profiles/decode_step_B1024.md"),
+    ("decay-path front of config 2", "wkv6_decay_lora_input_bf16"): (int(135334 * 1024 * 2.0 + 6144 * 1024 * 1.0), "profiles/decay_input_config2_tokens.md"),
     ("key compression M=32768 D=2048", "wkv6_key_compress_bf16"): (int(67636 * 1024 * 2.0 + 8192 * 1024 * 1.0), "profiles/key_compress_config2_tokens.md"),
 }
 KERNEL_CHUNK = 32               # tokens per chunk of the chunked kernel (for the matrix-core flop count)
@@ -193,6 +194,7 @@ def bench_decay_front(args, torch, wkv):
     abytes = M * D * 2 + M * 64 * 2 + B * D * 2 + 2 * D * 4 + (32 + 32 + 64) * D * 2
     aflops = 2 * M * D * (32 + 32 + 64)
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    traffic, traffic_source = profiled_traffic(f"decay-path front of config {cfg.index}", args.entry)
     result = {
         "metric": "decay-path front tokens/s (D=%d -> 32 -> D -> 64, bf16)" % D,
         "value": M / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -202,7 +204,7 @@ def bench_decay_front(args, torch, wkv):
         "config": {"workload": f"decay-path front of config {cfg.index}: B={B} T={T} D={D}", "entry": args.entry,
                    "global_batch": B, "seq_len": T},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "traffic_source": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms_avg": kernel_ms,
                      "per_launch_event_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
                      "per_launch_event_ms_min": min(per_launch_ms), "algorithmic_bytes": abytes,

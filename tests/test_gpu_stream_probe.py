@@ -1,7 +1,7 @@
 """Streaming microbenchmark (tests/stream_probe/stream_probe.hip): kernels that move the benchmark
-workload's bytes with no arithmetic, one workgroup per compute unit.  Its figures are what the design doc
-and profiles/ quote as the rate the memory system delivers to this access pattern; the test prints
-them and checks only that they are sane (every variant between 1 and 8 TB/s, the contiguous variant
+workload's bytes with no arithmetic, one workgroup per compute unit.  Its figures are the
+rate the memory system delivers to this access pattern, the reference beside which the kernel's
+time is read; the test prints them and checks only that they are sane (every variant between 1 and 8 TB/s, the contiguous variant
 not slower than the strided one by more than noise)."""
 import os
 import re

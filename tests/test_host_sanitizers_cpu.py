@@ -7,7 +7,7 @@ objects are built as usual and never run here).
   driver that calls every validation path (``tests/sanitize/boundary_check.cpp``); every call is
   rejected before a launch, so no GPU is needed.
 
-Commands (also what the design doc records):
+Commands:
   gcc -std=c11 -g -O1 -fsanitize=address,undefined -fno-sanitize-recover=all -pthread \
       tests/sanitize/oracle_check.c oracle/*.c -lm
   hipcc --offload-arch=gfx950 -O1 -g -std=c++17 -Xarch_host -fsanitize=address \
