@@ -227,6 +227,75 @@ def bench_decay_front(args, torch, wkv):
     print(json.dumps(result))
 
 
+def bench_layernorm_apply(args, torch, wkv):
+    """The LayerNorm of the output equation applied from per-token (mean, rstd): one streaming pass over
+    the read-outs of the chosen configuration (bf16 in, bf16 out, D = H*N)."""
+    import numpy as np
+    from oracle import layernorm_heads_numpy
+    from paper_2407_12077_amd.workloads import CONFIGS
+    cfg = CONFIGS[args.config]
+    B, T, H, N = cfg.B, cfg.T, cfg.H, cfg.N
+    D = H * N
+    eps = 1e-5
+    rng = np.random.Generator(np.random.PCG64(20240712 + 4000 + cfg.index))
+    nb, nt = 1, min(T, 256)                        # rows whose values come from the host (checked below)
+    o = torch.randn((B, T, H, N), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    head = (rng.standard_normal((nb, nt, H, N), dtype=np.float32) * np.float32(1.5) + np.float32(0.25))
+    o[:nb, :nt] = torch.from_numpy(head).to(torch.bfloat16).cuda()
+    of = o.float().view(B, T, D)
+    mean = of.mean(dim=2)
+    rstd = torch.rsqrt(of.var(dim=2, unbiased=False) + eps)
+    mr = torch.stack([mean, rstd], dim=2).contiguous()
+    del of
+    gamma = (1.0 + 0.3 * rng.standard_normal(D)).astype(np.float32)
+    beta = (0.2 * rng.standard_normal(D)).astype(np.float32)
+    g, bt = torch.from_numpy(gamma).cuda(), torch.from_numpy(beta).cuda()
+    y = torch.empty((B, T, D), dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        wkv.wkv6_layernorm_apply_bf16(B, T, H, N, o, mr, g, bt, y, wkv.WKV6_DTYPE_BF16, stream.cuda_stream)
+
+    preheat_launches = preheat(step, torch, args.preheat_ms)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    kernel_ms, ms_per_step, per_launch_ms = timed_region(step, args.steps, stream, torch)
+    M = B * T
+    abytes = M * D * 2 * 2 + M * 8 + 2 * D * 4
+    achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    result = {
+        "metric": "LayerNorm-apply tokens/s (D=%d, bf16 in and out)" % D,
+        "value": M / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "preheat_ms": args.preheat_ms, "preheat_launches": preheat_launches,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 tensors, f32 arithmetic", "data": "synthetic",
+        "config": {"workload": f"read-outs of config {cfg.index}: B={B} T={T} D={D}", "entry": args.entry,
+                   "global_batch": B, "seq_len": T},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "traffic_source": None,
+                     "kernel_ms_avg": kernel_ms,
+                     "per_launch_event_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
+                     "per_launch_event_ms_min": min(per_launch_ms), "algorithmic_bytes": abytes},
+    }
+    # the host-made rows against the oracle's LayerNorm over all heads (its own statistics, fp64)
+    ob = o[:nb, :nt].float().cpu().numpy()
+    ref, _, _ = layernorm_heads_numpy(ob, gamma, beta, eps)
+    got = y[:nb, :nt].float().cpu().numpy().reshape(ref.shape)
+    result["parity"] = {"tokens_checked": nb * nt, "err": float(np.abs(got - ref).max() / np.abs(ref).max()),
+                        "tolerance": 2.0 ** -8 + 1e-4, "against": "fp64 oracle LayerNorm of the same bf16 read-outs"}
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            layernorm_heads_numpy(ob, gamma, beta, eps)
+            reps += 1
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": reps * nb * nt / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"{reps} x {nb * nt} tokens, fp64 NumPy, {dt:.2f} s"}
+    print(json.dumps(result))
+
+
 def bench_key_compress(args, torch, wkv):
     """The step after the path: c = x W^KD for the tokens of the chosen configuration (B*T tokens,
     D = H*N), x and W^KD resident in HBM, bf16 output."""
@@ -301,7 +370,7 @@ def main():
                              "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
                              "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_moments",
                              "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16", "wkv6_decode_bf16", "wkv6_key_compress_bf16",
-                             "wkv6_decay_lora_input_bf16"])
+                             "wkv6_decay_lora_input_bf16", "wkv6_layernorm_apply_bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--preheat-ms", type=float, default=300.0,
                     help="untimed back-to-back launches of the step for this long before the warm-up steps")
@@ -326,6 +395,8 @@ def main():
         return bench_key_compress(args, torch, wkv)
     if args.entry == "wkv6_decay_lora_input_bf16":
         return bench_decay_front(args, torch, wkv)
+    if args.entry == "wkv6_layernorm_apply_bf16":
+        return bench_layernorm_apply(args, torch, wkv)
     cfg = CONFIGS[args.config]
     decode = args.entry == "wkv6_decode_bf16"
     if decode:

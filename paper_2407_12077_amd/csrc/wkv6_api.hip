@@ -206,7 +206,6 @@ int wkv6_layernorm_apply_bf16(int B, int T, int H, int N, const void* o, const f
     if (B < 0 || T < 0 || H < 1 || H > 262144) return WKV6_ERR_SHAPE;
     if (B == 0 || T == 0) return WKV6_OK;
     const long long tokens = static_cast<long long>(B) * T;
-    if ((tokens * (H * N / 8) + 255) / 256 > 0x7fffffffLL) return WKV6_ERR_SHAPE;               // grid size
     if (!o || !mean_rstd || !gamma || !beta || !y) return WKV6_ERR_NULL;
     if (misaligned(o) || misaligned(mean_rstd) || misaligned(gamma) || misaligned(beta) || misaligned(y))
         return WKV6_ERR_ALIGN;
