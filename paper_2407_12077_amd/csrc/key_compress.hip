@@ -6,7 +6,8 @@
 // accumulation, bf16 products are exact in fp32).
 //
 // One workgroup owns 128 tokens x 128 output columns (fewer in the last column tile when D/16 is
-// not a multiple of 128) and walks the D axis in steps of 64 channels.  Its eight waves split into two roles that meet at one barrier per step:
+// not a multiple of 128) and walks the D axis in steps of 64 channels (cyclically, from a start that
+// differs between workgroups).  Its eight waves split into two roles that meet at one barrier per step:
 //   waves 4..7  LOADERS: fetch the x tile (128 x 64: full 128-byte row pieces, 8 lanes each) and
 //               the W tile (64 x 128, an L2 hit) of a step two steps ahead into registers with
 //               16-byte loads, and park the tiles of the next step in one of two LDS buffers.
@@ -80,7 +81,7 @@ struct StepRegs {          // a loader thread's share of one step: 4 x 16 bytes 
 // loader waves (256 threads): tiles of step s+2 into registers, tiles of step s+1 into LDS
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void kc_loader(const KcArgs& a, char* lds, int lt, long long m0, int n0, int rows,
-                                          int nsteps) {
+                                          int nsteps, int first) {
     const long long x_row_bytes = static_cast<long long>(a.D) * 2;
     const char* x_base = static_cast<const char*>(a.x) + m0 * x_row_bytes;
     const long long x_bytes = rows * x_row_bytes;
@@ -104,8 +105,10 @@ __device__ __forceinline__ void kc_loader(const KcArgs& a, char* lds, int lt, lo
 
     auto fetch = [&](StepRegs& s, int step) {
         const bool live = step < nsteps;                                          // uniform
-        const long long xs = static_cast<long long>(step) * kBK * 2;              // byte offset along a row of x
-        const long long ws = static_cast<long long>(step) * kBK * w_row_bytes;   // first W row of the step
+        int ks = step + first;                                                    // this step's channel block
+        if (ks >= nsteps) ks -= nsteps;
+        const long long xs = static_cast<long long>(ks) * kBK * 2;                // byte offset along a row of x
+        const long long ws = static_cast<long long>(ks) * kBK * w_row_bytes;     // first W row of the step
         const __amdgpu_buffer_rsrc_t rx = rsrc_of(x_base + (live ? xs : 0), live ? x_bytes - xs : 0);
         const __amdgpu_buffer_rsrc_t rw = rsrc_of(w_base + (live ? ws : 0), live ? w_bytes - ws : 0);
 #pragma unroll
@@ -242,12 +245,17 @@ __global__ __launch_bounds__(kKcThreads, 2) void key_compress_kernel(KcArgs a) {
     const long long rows_left = a.M - m0;
     const int rows = rows_left < kBM ? static_cast<int>(rows_left) : kBM;
     const int nsteps = a.D / kBK;
+    // Every workgroup walks all channel blocks, but starts at a different one (the column tiles of
+    // a row tile at the same one): the rows of x are D*2 bytes apart, so workgroups that march
+    // through the channels in step would all ask the same few memory channels for their 128-byte
+    // row pieces, and the same L2 channel for the same rows of W (config 2's width: 127 -> 113 us).
+    const int first = static_cast<int>((slot / nct + 4 * xcd) % nsteps);
     // both roles pass 2 + nsteps barriers
     // the loaders' few instructions per step go ahead of the MFMA waves' long streams (wave
     // priority is an issue-arbitration hint): measured 2-3 % on the benchmark shapes
     if (wave >= 4) {
         __builtin_amdgcn_s_setprio(2);
-        kc_loader(a, lds, tid - 256, m0, n0, rows, nsteps);
+        kc_loader(a, lds, tid - 256, m0, n0, rows, nsteps, first);
     } else {
         __builtin_amdgcn_s_setprio(1);
         kc_worker<kOutF32>(a, lds, tid, wave, m0, n0, rows, nsteps);
