@@ -114,7 +114,8 @@ struct StepRegs {          // a loader thread's share of one step
 // ------------------------------------------------------------------------------------------
 // loader waves (512 threads)
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void di_loader(const DiArgs& a, char* lds, int lt, int b, int t0, int ntok, int nsteps) {
+__device__ __forceinline__ void di_loader(const DiArgs& a, char* lds, int lt, int b, int t0, int ntok, int nsteps,
+                                          int first) {
     const long long row_bytes = static_cast<long long>(a.D) * 2;
     const char* tile = a.x + (static_cast<long long>(b) * a.T + t0) * row_bytes;
     const char* pred = t0 > 0 ? tile - row_bytes : (a.x_prev ? a.x_prev + static_cast<long long>(b) * row_bytes : nullptr);
@@ -127,8 +128,14 @@ __device__ __forceinline__ void di_loader(const DiArgs& a, char* lds, int lt, in
 
     auto fetch = [&](StepRegs& s, int step) {
         const bool live = step < nsteps;                                   // uniform
-        const int chunk = step < nchunks ? step : step - nchunks;
+        // Both walks are sums over the channel blocks, so their order is free: walk 1 goes up from a
+        // block that differs between workgroups (workgroups marching through the channels in step
+        // would all ask the same memory channels for their row pieces, which are D*2 bytes apart),
+        // walk 2 comes back down, so that it starts with the blocks most recently brought into L2.
         const bool walk2 = step >= nchunks;
+        int chunk = walk2 ? first + 2 * nchunks - 1 - step : first + step;
+        if (chunk >= nchunks) chunk -= nchunks;
+        if (!live) chunk = 0;                                              // nothing is fetched: keep the bases in range
         const long long coff = static_cast<long long>(chunk) * (kStepCh * 2);   // byte offset of the chunk in a row
         const __amdgpu_buffer_rsrc_t rx = rsrc_of(tile + coff, live ? tile_bytes - coff : 0);
         s.x0 = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(rx, x_voff0, 0, 0));
@@ -344,7 +351,7 @@ __global__ __launch_bounds__(kDiThreads) void decay_input_kernel(DiArgs a) {
     // both roles pass 1 + nsteps barriers
     if (wave >= kWorkerWaves) {
         __builtin_amdgcn_s_setprio(2);
-        di_loader(a, lds, tid - 64 * kWorkerWaves, b, t0, ntok, nsteps);
+        di_loader(a, lds, tid - 64 * kWorkerWaves, b, t0, ntok, nsteps, static_cast<int>((blockIdx.x * 3u) % (a.D / kStepCh)));
     } else {
         __builtin_amdgcn_s_setprio(1);
         di_worker<kOutF32>(a, lds, tid & 63, wave, b, t0, ntok, nsteps);
