@@ -37,8 +37,10 @@ PROFILED_TRAFFIC = {
     ("config 2", "wkv6_prefill_bf16"): (int(262300 * 1024 * 2.0 + 135200 * 1024 * 1.0), "profiles/chunked_kernel_config2.md"),
     ("config 2", "wkv6_finch_c2_prefill_bf16"): (int(327806 * 1024 * 2.0 + 135168 * 1024 * 1.0), "profiles/finch_c2_kernel_config2.md"),
     ("decode-step B=1024", "wkv6_decode_bf16"): (int(270381 * 1024 * 2.0 + 528416 * 1024 * 1.0), "profiles/decode_step_B1024.md"),
-    ("decay-path front of config 2", "wkv6_decay_lora_input_bf16"): (int(135334 * 1024 * 2.0 + 6144 * 1024 * 1.0), "profiles/decay_input_config2_tokens.md"),
-    ("key compression M=32768 D=2048", "wkv6_key_compress_bf16"): (int(67636 * 1024 * 2.0 + 8192 * 1024 * 1.0), "profiles/key_compress_config2_tokens.md"),
+    ("decay-path front of config 2", "wkv6_decay_lora_input_bf16"): (int(126305 * 1024 * 2.0 + 6144 * 1024 * 1.0), "profiles/decay_input_config2_tokens.md"),
+    ("LayerNorm apply on config 2", "wkv6_layernorm_apply_bf16"): (int(65750 * 1024 * 2.0 + 131072 * 1024 * 1.0), "profiles/layernorm_apply_config2.md"),
+    ("key compression M=131072 D=2048", "wkv6_key_compress_bf16"): (int(265161 * 1024 * 2.0 + 32928 * 1024 * 1.0), "profiles/key_compress_131072_tokens.md"),
+    ("key compression M=131072 D=4096", "wkv6_key_compress_bf16"): (int(572103 * 1024 * 2.0 + 65546 * 1024 * 1.0), "profiles/key_compress_131072_tokens.md"),
 }
 KERNEL_CHUNK = 32               # tokens per chunk of the chunked kernel (for the matrix-core flop count)
 
@@ -264,6 +266,7 @@ def bench_layernorm_apply(args, torch, wkv):
     M = B * T
     abytes = M * D * 2 * 2 + M * 8 + 2 * D * 4
     achieved = abytes / (kernel_ms * 1e-3) / 1e9
+    traffic, traffic_source = profiled_traffic(f"LayerNorm apply on config {cfg.index}", args.entry)
     result = {
         "metric": "LayerNorm-apply tokens/s (D=%d, bf16 in and out)" % D,
         "value": M / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -273,7 +276,7 @@ def bench_layernorm_apply(args, torch, wkv):
         "config": {"workload": f"read-outs of config {cfg.index}: B={B} T={T} D={D}", "entry": args.entry,
                    "global_batch": B, "seq_len": T},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "traffic_source": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms_avg": kernel_ms,
                      "per_launch_event_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
                      "per_launch_event_ms_min": min(per_launch_ms), "algorithmic_bytes": abytes},
