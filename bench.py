@@ -378,6 +378,10 @@ def main():
     ap.add_argument("--preheat-ms", type=float, default=300.0,
                     help="untimed back-to-back launches of the step for this long before the warm-up steps")
     ap.add_argument("--tokens", type=int, default=0, help="key compression only: number of tokens M")
+    ap.add_argument("--aligned-placement", action="store_true",
+                    help="time separate allocations instead of the library's arena layout")
+    ap.add_argument("--no-placement-probe", action="store_true",
+                    help="skip the second timed region (plain prefill entries) with separately allocated tensors")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 512 MiB device copy (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -427,6 +431,27 @@ def main():
     s_out = torch.empty((B, H, N, N), dtype=torch.float32, device="cuda")
     fn = getattr(wkv, args.entry)
 
+    # The large tensors go where the library's placement helper puts them (one arena, tensor i at a
+    # 4 KiB boundary + 128 B x (i mod 8)), unless --aligned-placement asks for separate allocations.
+    staggered = not decode and not args.aligned_placement
+    plain = {"r": r, "k": k, "v": v, "x": x, "out": out}
+    if finch_c2:
+        plain["up"] = up
+    if staggered:
+        order = ["r", "k", "v", "x"] + (["up"] if finch_c2 else []) + ["out"]
+        sizes = [plain[n].numel() * plain[n].element_size() for n in order]
+        total, offsets = wkv.wkv6_arena_layout(sizes)
+        arena = torch.empty(total + 4096, dtype=torch.uint8, device="cuda")
+        first = (-arena.data_ptr()) % 4096
+        placed = {}
+        for n, off, nb in zip(order, offsets, sizes):
+            placed[n] = arena[first + off:first + off + nb].view(plain[n].dtype).view(plain[n].shape)
+            if n != "out":
+                placed[n].copy_(plain[n])
+        r, k, v, x, out = placed["r"], placed["k"], placed["v"], placed["x"], placed["out"]
+        if finch_c2:
+            up = placed["up"]
+
     stream = torch.cuda.current_stream()         # the stream the kernels are launched on
 
     if args.entry == "wkv6_prefill_bf16_split":
@@ -458,7 +483,7 @@ def main():
         lora = make_decay_lora_inputs(cfg)
         y, b_omega = dev(lora["y"], torch.bfloat16), dev(lora["b_omega"], torch.bfloat16)
         lam = dev(lora["lam"], torch.float32)
-        del x                                        # the logits are formed in the kernel
+        # x is not passed: the logits are formed in the kernel
 
         if finch_c2:
             def step():
@@ -518,7 +543,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index} ({cfg.name}): B={B} T={T} H={H} N={N}, "
                                f"{'nonzero' if s_in is not None else 'zero'} initial state",
-                   "entry": args.entry, "segments": segments, "global_batch": B, "seq_len": T},
+                   "entry": args.entry, "segments": segments, "global_batch": B, "seq_len": T,
+                   "placement": "wkv6_arena_layout: one arena, tensor i at a 4 KiB boundary + 128 B x (i mod 8)"
+                                if staggered else "separate allocations"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel_ms_avg": kernel_ms, "per_launch_event_ms_median": sorted(per_launch_ms)[len(per_launch_ms) // 2],
@@ -527,6 +554,23 @@ def main():
                      "mfma_frac": aflops / (kernel_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
     }
     result["parity"] = check_units(args, cfg, inp, out, s_out, finch_c2, decode, torch)
+    if staggered and args.entry in ("wkv6_prefill_bf16", "wkv6_finch_c2_prefill_bf16") and not args.no_placement_probe:
+        # Same call, same data, ordinary placement: every tensor an allocation of its own, so that all
+        # bases agree in address bits 7..9 (what a caller gets who does not use wkv6_arena_layout).
+        out_staggered, s_out_staggered = out, s_out.clone()
+        r, k, v, x, out = plain["r"], plain["k"], plain["v"], plain["x"], plain["out"]
+        if finch_c2:
+            up = plain["up"]
+        preheat(step, torch, args.preheat_ms)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        kernel_ms2, ms_per_step2, _ = timed_region(step, args.steps, stream, torch)
+        result["aligned_placement"] = {
+            "bases": "each tensor its own allocation (bases agree modulo 4 KiB)",
+            "ms_per_step": ms_per_step2, "value": B * T / (ms_per_step2 * 1e-3),
+            "frac": abytes / (kernel_ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "same_result": bool(torch.equal(out_staggered, out) and torch.equal(s_out_staggered, s_out))}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, finch_c2)
     print(json.dumps(result))

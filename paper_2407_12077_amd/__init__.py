@@ -7,4 +7,4 @@ from .binding import (  # noqa: F401
     wkv6_finch_c2_prefill_bf16_f32out, wkv6_finch_c2_prefill_bf16_strided, wkv6_prefill_bf16,
     wkv6_prefill_bf16_f32out, wkv6_prefill_bf16_recurrent, wkv6_prefill_lora_bf16, wkv6_prefill_bf16_split, wkv6_prefill_bf16_split_noalloc,
     wkv6_prefill_bf16_strided, wkv6_prefill_f32, wkv6_split_segments, wkv6_split_workspace_bytes,
-    wkv6_version)
+    wkv6_arena_layout, wkv6_version)

@@ -23,7 +23,8 @@ EXPORTS = ("wkv6_prefill_bf16", "wkv6_prefill_bf16_f32out", "wkv6_prefill_bf16_s
            "wkv6_finch_c2_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16_moments",
            "wkv6_layernorm_finalize", "wkv6_layernorm_apply_bf16", "wkv6_decay_lora_input_bf16", "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16",
            "wkv6_decode_bf16", "wkv6_finch_c2_decode_bf16", "wkv6_append_bf16",
-           "wkv6_finch_c2_append_bf16", "wkv6_key_compress_bf16", "wkv6_status_string", "wkv6_version")
+           "wkv6_finch_c2_append_bf16", "wkv6_key_compress_bf16", "wkv6_arena_layout", "wkv6_status_string",
+           "wkv6_version")
 
 _lib = None
 
@@ -83,6 +84,8 @@ def load():
         lib.wkv6_split_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.wkv6_split_segments.restype = i
         lib.wkv6_split_segments.argtypes = [i, i, i, i]
+        lib.wkv6_arena_layout.restype = ctypes.c_longlong
+        lib.wkv6_arena_layout.argtypes = [i, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(ctypes.c_longlong)]
         lib.wkv6_status_string.restype = ctypes.c_char_p
         lib.wkv6_status_string.argtypes = [i]
         lib.wkv6_version.restype = i
@@ -155,6 +158,15 @@ def wkv6_split_workspace_bytes(B, T, H, N, segments):
 
 def wkv6_split_segments(B, T, H, N):
     return load().wkv6_split_segments(B, T, H, N)
+
+
+def wkv6_arena_layout(sizes):
+    """(arena bytes, [offset of each tensor]) for tensors of the given byte sizes; (-1, []) if rejected."""
+    n = len(sizes)
+    arr = (ctypes.c_longlong * max(n, 1))(*[int(b) for b in sizes])
+    offs = (ctypes.c_longlong * max(n, 1))()
+    total = load().wkv6_arena_layout(n, arr, offs)
+    return total, ([int(offs[j]) for j in range(n)] if total >= 0 else [])
 
 
 def wkv6_prefill_f32(B, T, H, N, r, k, v, x, u, state_in, out, state_out, stream=None):

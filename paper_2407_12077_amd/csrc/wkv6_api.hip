@@ -289,6 +289,19 @@ int wkv6_decay_lora_input_bf16(int B, int T, int D, int R_d, int R, const void* 
     return err == hipSuccess ? WKV6_OK : WKV6_ERR_LAUNCH;
 }
 
+long long wkv6_arena_layout(int count, const long long* bytes, long long* offsets) {
+    if (count < 0 || count > 64) return -1;
+    if (count > 0 && (!bytes || !offsets)) return -1;
+    long long cursor = 0;
+    for (int i = 0; i < count; ++i) {
+        if (bytes[i] < 0 || bytes[i] > (1ll << 46)) return -1;
+        cursor = (cursor + WKV6_PLACEMENT_ALIGN - 1) / WKV6_PLACEMENT_ALIGN * WKV6_PLACEMENT_ALIGN;
+        offsets[i] = cursor + WKV6_PLACEMENT_STEP * (i % 8);
+        cursor = offsets[i] + bytes[i];
+    }
+    return (cursor + WKV6_PLACEMENT_ALIGN - 1) / WKV6_PLACEMENT_ALIGN * WKV6_PLACEMENT_ALIGN;
+}
+
 const char* wkv6_status_string(int status) {
     switch (status) {
         case WKV6_OK: return "ok";
@@ -302,7 +315,7 @@ const char* wkv6_status_string(int status) {
     }
 }
 
-int wkv6_version(void) { return 430; }
+int wkv6_version(void) { return 500; }
 
 }  // extern "C"
 

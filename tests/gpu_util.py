@@ -59,6 +59,23 @@ def to_dev(a, dtype):
     return t.to(dtype).cuda()
 
 
+def in_arena(tensors):
+    """Copies of the given device tensors inside one arena, placed by the library's wkv6_arena_layout
+    (4 KiB slots, tensor i shifted by 128 (i mod 8) bytes).  Returns (arena, [views])."""
+    import paper_2407_12077_amd as wkv
+    sizes = [t.numel() * t.element_size() for t in tensors]
+    total, offs = wkv.wkv6_arena_layout(sizes)
+    assert total >= 0
+    arena = torch.empty(total + 4096, dtype=torch.uint8, device="cuda")
+    first = (-arena.data_ptr()) % 4096
+    views = []
+    for t, o, b in zip(tensors, offs, sizes):
+        v = arena[first + o:first + o + b].view(t.dtype).view(t.shape)
+        v.copy_(t)
+        views.append(v)
+    return arena, views
+
+
 def run_entry(entry, inp, out_dtype=torch.float32, in_dtype=torch.bfloat16, want_state=True,
               inplace_state=False):
     """Run one entry point on the arrays of ``inp`` (dict from make_inputs).  Returns

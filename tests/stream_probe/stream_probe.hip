@@ -94,17 +94,19 @@ int main(int argc, char** argv) {
     const int launches = argc > 1 ? std::atoi(argv[1]) : 50;
     const size_t bytes = 8ull * kSeqBytes;                     // 128 MiB per stream
     Params p;
-    for (int i = 0; i < 4; ++i) {
-        char* q = nullptr;
-        CHECK_HIP(hipMalloc(reinterpret_cast<void**>(&q), bytes));
-        CHECK_HIP(hipMemset(q, i + 1, bytes));
-        p.in[i] = q;
+    char* raw[5];                                              // four inputs and the output, 4 KiB of slack each
+    for (int i = 0; i < 5; ++i) {
+        CHECK_HIP(hipMalloc(reinterpret_cast<void**>(&raw[i]), bytes + 4096));
+        CHECK_HIP(hipMemset(raw[i], i + 1, bytes + 4096));
     }
-    CHECK_HIP(hipMalloc(reinterpret_cast<void**>(&p.out), bytes));
     hipEvent_t e0, e1;
     CHECK_HIP(hipEventCreate(&e0));
     CHECK_HIP(hipEventCreate(&e1));
-    auto run = [&](const char* name, auto kernel, int row_bytes, int inputs, int outputs) {
+    // stagger: bytes by which the i-th buffer's base is shifted (0: all bases agree modulo 4 KiB, as
+    // tensors from an allocator do)
+    auto run = [&](const char* name, auto kernel, int row_bytes, int inputs, int outputs, int stagger = 0) {
+        for (int i = 0; i < 4; ++i) p.in[i] = raw[i] + i * stagger;
+        p.out = raw[4] + 4 * stagger;
         p.row_bytes = row_bytes;
         p.inputs = inputs;
         p.outputs = outputs;
@@ -133,5 +135,7 @@ int main(int argc, char** argv) {
     run("contiguous slabs, nt loads, write-through stores", stream_kernel<4, 2, 16>, 4096, 4, 1);
     run("kernel layout, the four input streams only", stream_kernel<4, 2, 16>, 128, 4, 0);
     run("kernel layout, the output stream only", stream_kernel<4, 2, 16>, 128, 0, 1);
+    run("kernel layout, buffer bases 128 B apart modulo 1 KiB", stream_kernel<4, 2, 16>, 128, 4, 1, 128);
+    run("contiguous slabs, buffer bases 128 B apart modulo 1 KiB", stream_kernel<4, 2, 16>, 4096, 4, 1, 128);
     return 0;
 }

@@ -124,6 +124,24 @@ def test_oracle_is_not_reachable_from_the_product():
                     f"{fn} reaches into the oracle"
 
 
+def test_arena_layout():
+    """The placement helper: 4 KiB-aligned slots, tensor i shifted by 128 (i mod 8) bytes, no overlap,
+    total a multiple of 4 KiB; rejected argument sets return -1."""
+    sizes = [1000, 4096, 1, 0, 134217728, 77, 4097, 5, 12345, 16]
+    total, offs = wkv.wkv6_arena_layout(sizes)
+    assert total % 4096 == 0 and len(offs) == len(sizes)
+    end = 0
+    for j, (o, b) in enumerate(zip(offs, sizes)):
+        assert o % 4096 == 128 * (j % 8) and o >= end and o - end < 4096 + 1024
+        end = o + b
+    assert end <= total < end + 4096
+    assert {o % 1024 for o in offs[:6]} == {0, 128, 256, 384, 512, 640}      # six streams, six different eighths
+    assert wkv.wkv6_arena_layout([]) == (0, [])
+    assert wkv.wkv6_arena_layout([10, -1])[0] == -1
+    assert wkv.wkv6_arena_layout([1] * 65)[0] == -1
+    assert binding.load().wkv6_arena_layout(2, None, None) == -1
+
+
 def test_split_helpers_and_validation():
     lib = binding.load()
     assert wkv.wkv6_split_segments(1, 131072, 32, 64) == 8          # 32 units on 256 CUs

@@ -402,3 +402,37 @@ def test_many_units_in_place_state_and_zero_state(gpu_device):
     assert max_norm_err(o, o_ref) <= TOL_BF16 and max_norm_err(s, s_ref) <= TOL_BF16
     inp["state_in"] = None
     check("wkv6_prefill_bf16_f32out", inp, TOL_BF16)
+
+
+@pytest.mark.parametrize("entry", ["wkv6_prefill_bf16", "wkv6_finch_c2_prefill_bf16"])
+def test_result_does_not_depend_on_placement(gpu_device, entry):
+    """The same call with its tensors at the library's staggered arena offsets (bases that differ in
+    address bits 7..9) and with ordinary, equally aligned tensors: identical bits."""
+    from gpu_util import in_arena
+    import paper_2407_12077_amd as wkv
+    from paper_2407_12077_amd.workloads import make_uprime
+    cfg = scaled(CONFIGS[2], B=3, T=700, H=12)
+    inp = make_inputs(cfg, seed=77)
+    c2 = "finch_c2" in entry
+    B, T, H, N = inp["r"].shape
+    names = ["r", "k", "v", "x"]
+    if c2:
+        inp["uprime"] = make_uprime(cfg, seed=78)
+        names.append("uprime")
+    plain = [to_dev(inp[n], torch.bfloat16) for n in names]
+    u = to_dev(inp["u"], torch.float32)
+    outs = []
+    for staggered in (False, True):
+        out = torch.full((B, T, H, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        if staggered:
+            arena, views = in_arena(plain + [out])
+            ins, out = views[:-1], views[-1]
+            assert len({v.data_ptr() % 1024 for v in views}) == len(views)
+        else:
+            ins = plain
+        s_out = torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda")
+        getattr(wkv, entry)(B, T, H, N, ins[0], ins[1], ins[2], ins[3], ins[4] if c2 else u, None, out, s_out)
+        torch.cuda.synchronize()
+        outs.append((out.clone(), s_out))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert torch.isfinite(outs[0][0].float()).all()

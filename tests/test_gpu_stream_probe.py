@@ -25,7 +25,7 @@ def test_stream_probe_rates(gpu_device):
         m = re.match(r"(.*?)\s+([\d.]+) us\s+([\d.]+) TB/s", line)
         if m:
             rates[m.group(1).strip()] = float(m.group(3))
-    assert len(rates) == 8
+    assert len(rates) == 10
     assert all(1.0 < v < 8.0 for v in rates.values()), rates
     strided = rates["kernel layout (128 B rows), nt loads, write-through stores"]
     slabs = rates["contiguous slabs, nt loads, write-through stores"]
