@@ -142,18 +142,19 @@ __device__ __forceinline__ unsigned pack_bf2(float a, float b) {
 // w = exp(-exp(x)) through two base-2 exponentials (x=-inf -> 1, x=+inf -> 0):
 // log2(e) * exp(x) = exp2(x * log2(e) + log2(log2(e))), so the factor of the second exponential
 // rides in the argument of the first.
-__device__ __forceinline__ float decay_of(float x) {
+// Also hands back the scaled inner exponential log2(e) * exp(x), which the Finch-C2 key factor needs.
+__device__ __forceinline__ float decay_of(float x, float& e_log2e) {
     constexpr float kLog2Log2e = 0.5287663729448977f;
-    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, kLog2Log2e));
-    return __builtin_amdgcn_exp2f(-e);
+    e_log2e = __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, kLog2Log2e));
+    return __builtin_amdgcn_exp2f(-e_log2e);
 }
 
 // Finch-C2 key factor 1 - w = 1 - exp(-e), e = exp(x), without the cancellation of the plain
 // subtraction for long-memory channels (w close to 1): below e = 2^-5 the alternating series
 // e (1 - e/2 + e^2/6 - e^3/24), whose first dropped term is under 1e-8 of the result there;
 // above it the subtraction loses at most five bits of an fp32 value.
-__device__ __forceinline__ float one_minus_decay(float x, float w) {
-    const float e = __builtin_amdgcn_exp2f(x * kLog2e);
+__device__ __forceinline__ float one_minus_decay(float e_log2e, float w) {
+    const float e = e_log2e * 0.6931471805599453f;      // exp(x) from the decay's own inner exponential
     const float series = e * __builtin_fmaf(e, __builtin_fmaf(e, __builtin_fmaf(e, -1.f / 24.f, 1.f / 6.f), -0.5f), 1.f);
     return e < 0.03125f ? series : 1.f - w;
 }
@@ -404,21 +405,24 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const bool past = t0 + 4 * g8 + s >= T;          // tokens past the end: w = 1
-                w[0][s] = past ? 1.f : decay_of(d0[s]);
-                w[1][s] = past ? 1.f : decay_of(d1[s]);
+                float e0 = 0.f, e1 = 0.f;
+                const float w0 = decay_of(d0[s], e0), w1 = decay_of(d1[s], e1);
+                w[0][s] = past ? 1.f : w0;
+                w[1][s] = past ? 1.f : w1;
                 if constexpr (kC2) {
-                    omw[0][s] = one_minus_decay(d0[s], w[0][s]);       // past the end the key is zero
-                    omw[1][s] = one_minus_decay(d1[s], w[1][s]);
+                    omw[0][s] = one_minus_decay(e0, w0);               // past the end the key is zero
+                    omw[1][s] = one_minus_decay(e1, w1);
                 }
             }
         } else {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                w[0][s] = decay_of(bf16_lo(cur.x[s]));
-                w[1][s] = decay_of(bf16_hi(cur.x[s]));
+                float e0 = 0.f, e1 = 0.f;
+                w[0][s] = decay_of(bf16_lo(cur.x[s]), e0);
+                w[1][s] = decay_of(bf16_hi(cur.x[s]), e1);
                 if constexpr (kC2) {
-                    omw[0][s] = one_minus_decay(bf16_lo(cur.x[s]), w[0][s]);
-                    omw[1][s] = one_minus_decay(bf16_hi(cur.x[s]), w[1][s]);
+                    omw[0][s] = one_minus_decay(e0, w[0][s]);
+                    omw[1][s] = one_minus_decay(e1, w[1][s]);
                 }
             }
         }
@@ -474,7 +478,11 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         }
     };
 
-    // Phase T: multipliers from the other groups' decay totals, then every operand tile.  The
+    // Phase T: multipliers from the other groups' decay totals, then every operand tile.  (Writing
+    // the four tiles that need no totals -- Z4, Z2, Q1, K1 -- a window earlier, in phase D, into a
+    // slot per producer group was measured and dropped: the digest phase grew by what the tile
+    // phase should have lost and the window did not get shorter; the compute unit's LDS queue, not
+    // one phase's share of it, is what the window waits for.)  The
     // body is instantiated per wave position kWq so that the level-8 and level-16 roles (key or
     // query side) and the neighbouring group products are compile-time choices.
     auto write_tiles_at = [&](auto wq_const, int c) {
