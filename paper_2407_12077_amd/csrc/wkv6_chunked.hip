@@ -482,7 +482,10 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // the four tiles that need no totals -- Z4, Z2, Q1, K1 -- a window earlier, in phase D, into a
     // slot per producer group was measured and dropped: the digest phase grew by what the tile
     // phase should have lost and the window did not get shorter; the compute unit's LDS queue, not
-    // one phase's share of it, is what the window waits for.)  The
+    // one phase's share of it, is what the window waits for.  Also measured and dropped: neighbouring
+    // lanes trading two values so that each token-row tile takes two 8-byte stores instead of four
+    // 4-byte ones -- 9 % slower in the kernel although 8-byte stores run at 85 against 62 B/clk in
+    // isolation.)  The
     // body is instantiated per wave position kWq so that the level-8 and level-16 roles (key or
     // query side) and the neighbouring group products are compile-time choices.
     auto write_tiles_at = [&](auto wq_const, int c) {
