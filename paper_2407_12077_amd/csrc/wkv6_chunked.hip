@@ -619,7 +619,11 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
     // Phase S, part 2.  Finished output rows of chunk c (staged by the consumers): full
     // 128-byte (bf16) rows to HBM, 8 threads per row.  Finch-C2: the rows are staged in fp32 and
     // the second value u' of the same 8 channels (16 bytes, loaded two windows earlier) is added
-    // before the single rounding of the output.
+    // before the single rounding of the output.  (Letting the consumer waves load u' in their
+    // accumulator layout and start the chunk's accumulator from it -- bf16 staging, nothing to add
+    // here -- gives the same bits and was 25 % slower: a load issued by any wave of the workgroup
+    // returns behind the chunk loads the producers already have in flight, four to six windows
+    // of them, and the consumers cannot wait that long.)
     const int srow = gtid >> 3;                  // token row inside the chunk this thread stores
     const int scol = 8 * (gtid & 7);             // first of its 8 channels
     [[maybe_unused]] uint4v up_raw = {0u, 0u, 0u, 0u};
