@@ -473,8 +473,13 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         // and on the key for odd tokens, so the diagonal gets r.u.k and the pair gets plain r.k
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            pr.q1[s] = (kC2 || (s & 1)) ? rh[s] : mul_h2(rh[s], hu);
-            pr.k1[s] = (kC2 || !(s & 1)) ? kh[s] : mul_h2(kh[s], hu);
+            if constexpr (kC2) {
+                // no diagonal term: one tile, keys in the even token rows, receptances in the odd ones
+                pr.q1[s] = (s & 1) ? rh[s] : kh[s];
+            } else {
+                pr.q1[s] = (s & 1) ? rh[s] : mul_h2(rh[s], hu);
+                pr.k1[s] = !(s & 1) ? kh[s] : mul_h2(kh[s], hu);
+            }
         }
     };
 
@@ -520,7 +525,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                  q4 ? pr.rp[3] : pr.ks[3]);
             put4(kZ2, pr.z2[0], pr.z2[1], pr.z2[2], pr.z2[3]);
             put4(kQ1, pr.q1[0], pr.q1[1], pr.q1[2], pr.q1[3]);
-            put4(kK1, pr.k1[0], pr.k1[1], pr.k1[2], pr.k1[3]);
+            if constexpr (!kC2) put4(kK1, pr.k1[0], pr.k1[1], pr.k1[2], pr.k1[3]);
         }
         __builtin_amdgcn_sched_barrier(0);       // keep these writes ahead of the wait for the totals
 #pragma unroll
@@ -589,7 +594,7 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         const half8 z4 = lds_read_h8(lds, kZ4 + rowq);
         const half8 z2 = lds_read_h8(lds, kZ2 + rowq);
         const half8 q1 = lds_read_h8(lds, kQ1 + rowq);
-        const half8 k1 = lds_read_h8(lds, kK1 + rowq);
+        const half8 k1 = kC2 ? q1 : lds_read_h8(lds, kK1 + rowq);
         const float4v zero{0.f, 0.f, 0.f, 0.f};
         const float4v acc8 = mfma(z8, z8, zero);
         const float4v acc4 = mfma(z4, z4, zero);
