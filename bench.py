@@ -299,6 +299,116 @@ def bench_layernorm_apply(args, torch, wkv):
     print(json.dumps(result))
 
 
+def bench_chain(args, torch, wkv):
+    """The data path of one Finch-C2 time-mix layer with everything this library builds, as one step on
+    one stream: decay front (x -> y), fused prefill with the LayerNorm partials (r, kbar, v, y, u' ->
+    out, state), their fold, the normalisation, and -- standing in for the step behind the layer stack,
+    on the normalised rows as hidden states -- the key compression.  Reports the step and each call."""
+    import numpy as np
+    from oracle import (decay_logits_numpy, decay_lora_input_numpy, finch_c2_oracle, key_compress_oracle,
+                        layernorm_heads_numpy)
+    from paper_2407_12077_amd.workloads import (CONFIGS, make_decay_front_inputs, make_decay_lora_inputs, make_inputs,
+                                                make_key_compress_inputs, make_uprime, round_to_bf16)
+    cfg = CONFIGS[args.config]
+    B, T, H, N = cfg.B, cfg.T, cfg.H, cfg.N
+    D, M, C, R, eps = H * N, B * T, H * N // 16, 64, 1e-5
+    fi, inp, lo = make_decay_front_inputs(cfg), make_inputs(cfg), make_decay_lora_inputs(cfg)
+    uprime = make_uprime(cfg)
+    _, w_kd = make_key_compress_inputs(16, D)
+    rng = np.random.Generator(np.random.PCG64(20240712 + 5000 + cfg.index))
+    gamma = (1.0 + 0.3 * rng.standard_normal(D)).astype(np.float32)
+    beta = (0.2 * rng.standard_normal(D)).astype(np.float32)
+    dev = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(dt).cuda()
+    bf, f32 = torch.bfloat16, torch.float32
+    # the large [B][T][D] tensors in one arena laid out by the library (see wkv6_arena_layout)
+    shapes = {"x": (B, T, D), "r": (B, T, H, N), "k": (B, T, H, N), "v": (B, T, H, N), "up": (B, T, H, N),
+              "out": (B, T, H, N), "ln": (B, T, D)}
+    total, offs = wkv.wkv6_arena_layout([M * D * 2] * len(shapes))
+    arena = torch.empty(total + 4096, dtype=torch.uint8, device="cuda")
+    first = (-arena.data_ptr()) % 4096
+    t = {n: arena[first + o:first + o + M * D * 2].view(bf).view(sh) for (n, sh), o in zip(shapes.items(), offs)}
+    for n, src in (("x", fi["x"]), ("r", inp["r"]), ("k", inp["k"]), ("v", inp["v"]), ("up", uprime)):
+        t[n].copy_(dev(src, bf).view(shapes[n]))
+    xp, mu, lam_d = dev(fi["x_prev"], bf), dev(fi["mu_x"], f32), dev(fi["lam_d"], f32)
+    a_d, b_d, a_w = (dev(fi[n].T, bf) for n in ("A_d", "B_d", "A_omega"))
+    lam_w, b_w = dev(lo["lam"], f32), dev(lo["b_omega"], bf)
+    g, bt, wkd = dev(gamma, f32), dev(beta, f32), dev(w_kd, bf)
+    y = torch.empty((B, T, R), dtype=bf, device="cuda")
+    mom = torch.empty((B, H, T, 2), dtype=f32, device="cuda")
+    mr = torch.empty((B, T, 2), dtype=f32, device="cuda")
+    s_out = torch.empty((B, H, N, N), dtype=f32, device="cuda")
+    c = torch.empty((M, C), dtype=bf, device="cuda")
+    stream = torch.cuda.current_stream()
+    q = stream.cuda_stream
+    calls = [
+        ("wkv6_decay_lora_input_bf16", lambda: wkv.wkv6_decay_lora_input_bf16(B, T, D, 32, R, t["x"], xp, mu, lam_d, a_d, b_d, a_w, y, wkv.WKV6_DTYPE_BF16, q)),
+        ("wkv6_finch_c2_prefill_lora_bf16", lambda: wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, R, t["r"], t["k"], t["v"], y, lam_w, b_w, t["up"], None, t["out"], mom, s_out, q)),
+        ("wkv6_layernorm_finalize", lambda: wkv.wkv6_layernorm_finalize(B, T, H, N, mom, eps, mr, q)),
+        ("wkv6_layernorm_apply_bf16", lambda: wkv.wkv6_layernorm_apply_bf16(B, T, H, N, t["out"], mr, g, bt, t["ln"], wkv.WKV6_DTYPE_BF16, q)),
+        ("wkv6_key_compress_bf16", lambda: wkv.wkv6_key_compress_bf16(M, D, t["ln"], wkd, c, wkv.WKV6_DTYPE_BF16, q)),
+    ]
+
+    def step():
+        for _, f in calls:
+            f()
+
+    preheat_launches = preheat(step, torch, args.preheat_ms)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    kernel_ms, ms_per_step, _ = timed_region(step, args.steps, stream, torch)
+    per_call = {}
+    for name, f in calls:                          # each call alone, back to back, for the breakdown
+        for _ in range(20):
+            f()
+        torch.cuda.synchronize()
+        per_call[name], _, _ = timed_region(f, min(args.steps, 100), stream, torch)
+    step()
+    torch.cuda.synchronize()
+    abytes = {"wkv6_decay_lora_input_bf16": M * D * 2 + M * R * 2 + (32 + 32 + R) * D * 2,
+              "wkv6_finch_c2_prefill_lora_bf16": 5 * M * D * 2 + M * R * 2 + R * D * 2 + B * H * N * N * 4 + M * H * 8,
+              "wkv6_layernorm_finalize": M * H * 8 + M * 8,
+              "wkv6_layernorm_apply_bf16": 2 * M * D * 2 + M * 8,
+              "wkv6_key_compress_bf16": M * D * 2 + D * C * 2 + M * C * 2}
+    total_bytes = sum(abytes.values())
+    achieved = total_bytes / (kernel_ms * 1e-3) / 1e9
+    result = {
+        "metric": "Finch-C2 time-mix chain tokens/s per layer (H=%d,N=%d,bf16): decay front, fused prefill, LayerNorm, "
+                  "key compression" % (H, N),
+        "value": M / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "preheat_ms": args.preheat_ms, "preheat_launches": preheat_launches, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 tensors; f16/bf16 MFMA operands, f32 accumulate and state", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} ({cfg.name}): B={B} T={T} H={H} N={N}, five calls per step",
+                   "entry": "chain", "global_batch": B, "seq_len": T, "placement": "wkv6_arena_layout"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "traffic_source": None, "kernel_ms_avg": kernel_ms, "algorithmic_bytes": total_bytes,
+                     "per_call": {n: {"ms": per_call[n], "algorithmic_bytes": abytes[n],
+                                      "frac": abytes[n] / (per_call[n] * 1e-3) / 1e9 / HBM_PEAK_GBS} for n, _ in calls}},
+    }
+    # the first nt tokens of the first sequence through the chained oracles (each stage fed the rounding the
+    # GPU's interface tensor carries, so a stage's error is its own)
+    nt = min(T, 1024)
+    sl = lambda a: a[:1, :nt]
+    y_ref = decay_lora_input_numpy(sl(fi["x"]), fi["x_prev"][:1], fi["mu_x"], fi["lam_d"], fi["A_d"], fi["B_d"], fi["A_omega"])
+    y_gpu = y[:1, :nt].float().cpu().numpy()
+    d = decay_logits_numpy(y_gpu, lo["lam"], lo["b_omega"], H, N)
+    o_ref, _ = finch_c2_oracle(sl(inp["r"]), sl(inp["k"]), sl(inp["v"]), d.astype(np.float32), sl(uprime), None)
+    o_gpu = t["out"][:1, :nt].float().cpu().numpy()
+    ln_ref, _, _ = layernorm_heads_numpy(o_gpu, gamma, beta, eps)
+    ln_gpu = t["ln"][:1, :nt].float().cpu().numpy().reshape(1, nt, H, N)
+    c_ref = key_compress_oracle(ln_gpu.reshape(nt, D), w_kd)
+    c_gpu = c[:nt].float().cpu().numpy()
+    err = lambda got, ref: float(np.abs(got - ref).max() / np.abs(ref).max())
+    result["parity"] = {"tokens_checked": nt, "err_y": err(y_gpu, y_ref), "err_out": err(o_gpu, o_ref),
+                        "err_layernorm": err(ln_gpu, ln_ref), "err_compressed": err(c_gpu, c_ref),
+                        "tolerance": 2e-3 + 2.0 ** -8,
+                        "against": "fp64 oracles, stage by stage on the GPU's own interface tensors, bf16 outputs"}
+    result["parity"]["ok"] = all(result["parity"][k] <= result["parity"]["tolerance"]
+                                 for k in ("err_y", "err_out", "err_layernorm", "err_compressed"))
+    print(json.dumps(result))
+
+
 def bench_key_compress(args, torch, wkv):
     """The step after the path: c = x W^KD for the tokens of the chosen configuration (B*T tokens,
     D = H*N), x and W^KD resident in HBM, bf16 output."""
@@ -373,7 +483,7 @@ def main():
                              "wkv6_prefill_bf16_split", "wkv6_finch_c2_prefill_bf16",
                              "wkv6_finch_c2_prefill_bf16_f32out", "wkv6_finch_c2_prefill_bf16_moments",
                              "wkv6_finch_c2_prefill_lora_bf16", "wkv6_prefill_lora_bf16", "wkv6_decode_bf16", "wkv6_key_compress_bf16",
-                             "wkv6_decay_lora_input_bf16", "wkv6_layernorm_apply_bf16"])
+                             "wkv6_decay_lora_input_bf16", "wkv6_layernorm_apply_bf16", "chain"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--preheat-ms", type=float, default=300.0,
                     help="untimed back-to-back launches of the step for this long before the warm-up steps")
@@ -404,6 +514,8 @@ def main():
         return bench_decay_front(args, torch, wkv)
     if args.entry == "wkv6_layernorm_apply_bf16":
         return bench_layernorm_apply(args, torch, wkv)
+    if args.entry == "chain":
+        return bench_chain(args, torch, wkv)
     cfg = CONFIGS[args.config]
     decode = args.entry == "wkv6_decode_bf16"
     if decode:
