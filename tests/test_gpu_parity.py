@@ -436,3 +436,32 @@ def test_result_does_not_depend_on_placement(gpu_device, entry):
         outs.append((out.clone(), s_out))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
     assert torch.isfinite(outs[0][0].float()).all()
+
+
+def test_split_result_does_not_depend_on_placement(gpu_device):
+    """The token split (three launches, caller workspace) with its tensors at the library's staggered
+    arena offsets and with ordinary tensors: identical bits, out and final state."""
+    from gpu_util import in_arena
+    import paper_2407_12077_amd as wkv
+    cfg = scaled(CONFIGS[3], T=3000, H=4)
+    inp = make_inputs(cfg, seed=91)
+    B, T, H, N = inp["r"].shape
+    plain = [to_dev(inp[n], torch.bfloat16) for n in ("r", "k", "v", "x")]
+    u = to_dev(inp["u"], torch.float32)
+    segments = 5
+    ws_bytes = wkv.wkv6_split_workspace_bytes(B, T, H, N, segments)
+    results = []
+    for staggered in (False, True):
+        out = torch.full((B, T, H, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ins = plain
+        if staggered:
+            arena, views = in_arena(plain + [out])
+            ins, out = views[:-1], views[-1]
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        s_out = torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda")
+        wkv.wkv6_prefill_bf16_split(B, T, H, N, ins[0], ins[1], ins[2], ins[3], u, None, out, s_out,
+                                    wkv.WKV6_DTYPE_BF16, segments, ws, ws_bytes)
+        torch.cuda.synchronize()
+        results.append((out.clone(), s_out))
+    assert torch.equal(results[0][0], results[1][0]) and torch.equal(results[0][1], results[1][1])
+    assert torch.isfinite(results[0][0].float()).all() and torch.isfinite(results[0][1]).all()
