@@ -135,3 +135,58 @@ def test_fused_layer_pieces_in_a_graph(gpu_device):
         torch.cuda.synchronize()
         for a, b in zip(captured, eager):
             assert torch.equal(a, b), replay
+
+
+def test_layer_chain_in_a_graph(gpu_device):
+    """All five calls of a Finch-C2 time-mix layer (decay front, fused prefill with LayerNorm partials,
+    fold, normalisation, key compression) captured as one graph."""
+    from paper_2407_12077_amd.workloads import (make_decay_front_inputs, make_decay_lora_inputs,
+                                                make_key_compress_inputs, make_uprime)
+    cfg = scaled(CONFIGS[2], B=2, T=200, H=4)
+    B, T, H, N = cfg.B, cfg.T, cfg.H, cfg.N
+    D, M = H * N, B * T
+    fi, inp, lo = make_decay_front_inputs(cfg), make_inputs(cfg), make_decay_lora_inputs(cfg)
+    bf, f32 = torch.bfloat16, torch.float32
+    x, xp = to_dev(fi["x"], bf), to_dev(fi["x_prev"], bf)
+    mu, lam_d = to_dev(fi["mu_x"], f32), to_dev(fi["lam_d"], f32)
+    a_d, b_d, a_w = (to_dev(np.ascontiguousarray(fi[n].T), bf) for n in ("A_d", "B_d", "A_omega"))
+    r, k, v, up = (to_dev(a, bf) for a in (inp["r"], inp["k"], inp["v"], make_uprime(cfg)))
+    lam_w, b_w = to_dev(lo["lam"], f32), to_dev(lo["b_omega"], bf)
+    gamma, beta = torch.ones(D, device="cuda"), torch.zeros(D, device="cuda")
+    w_kd = to_dev(make_key_compress_inputs(16, D)[1], bf)
+
+    def fresh():
+        nan = lambda shape, dt: torch.full(shape, float("nan"), dtype=dt, device="cuda")
+        return (nan((B, T, 64), bf), nan((B, T, H, N), bf), nan((B, H, T, 2), f32), nan((B, T, 2), f32),
+                nan((B, H, N, N), f32), nan((B, T, D), bf), nan((M, D // 16), bf))
+
+    def run(bufs):
+        y, out, mom, mr, s_out, ln, c = bufs
+        wkv.wkv6_decay_lora_input_bf16(B, T, D, 32, 64, x, xp, mu, lam_d, a_d, b_d, a_w, y, wkv.WKV6_DTYPE_BF16)
+        wkv.wkv6_finch_c2_prefill_lora_bf16(B, T, H, N, 64, r, k, v, y, lam_w, b_w, up, None, out, mom, s_out)
+        wkv.wkv6_layernorm_finalize(B, T, H, N, mom, 1e-5, mr)
+        wkv.wkv6_layernorm_apply_bf16(B, T, H, N, out, mr, gamma, beta, ln, wkv.WKV6_DTYPE_BF16)
+        wkv.wkv6_key_compress_bf16(M, D, ln, w_kd, c, wkv.WKV6_DTYPE_BF16)
+
+    eager = fresh()
+    run(eager)
+    torch.cuda.synchronize()
+    assert all(torch.isfinite(t.float()).all() for t in eager)
+    captured = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(captured)                             # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(captured)
+    for replay in range(3):
+        for t in captured:
+            t.fill_(float("nan"))                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(captured, eager):
+            assert torch.equal(a, b), replay
