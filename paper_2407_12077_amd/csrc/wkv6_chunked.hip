@@ -664,8 +664,12 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
         };
         if (t < T) {
             if constexpr (kStageF32) {
-                const float4* src = reinterpret_cast<const float4*>(lds + kO + (srow * kORowF32 + scol) * 4);
-                float4 q0 = src[0], q1 = src[1];
+                // fp32 rows of the Finch form (256 bytes): the row's 8 threads store its first 128 bytes, then
+                // its second (whole cache lines per instruction): thread j holds floats 4j.. and 32 + 4j..
+                constexpr bool kSplitRow = kOutF32 && !kC2;
+                const float4* src = reinterpret_cast<const float4*>(
+                    lds + kO + (srow * kORowF32 + (kSplitRow ? scol / 2 : scol)) * 4);
+                float4 q0 = src[0], q1 = src[kSplitRow ? 8 : 1];
                 if constexpr (kC2) {
                     q0.x += bf16_lo(up_raw[0]); q0.y += bf16_hi(up_raw[0]);
                     q0.z += bf16_lo(up_raw[1]); q0.w += bf16_hi(up_raw[1]);
@@ -698,8 +702,13 @@ __device__ __forceinline__ void producer(const Args& a, char* lds_all, int tid, 
                     }
                 }
                 if constexpr (kOutF32) {
-                    put(__builtin_bit_cast(uint4v, q0), 0);
-                    put(__builtin_bit_cast(uint4v, q1), 16);
+                    if constexpr (kSplitRow) {
+                        put(__builtin_bit_cast(uint4v, q0), -scol * 2);            // byte 16 j of the row
+                        put(__builtin_bit_cast(uint4v, q1), 128 - scol * 2);      // byte 128 + 16 j
+                    } else {
+                        put(__builtin_bit_cast(uint4v, q0), 0);
+                        put(__builtin_bit_cast(uint4v, q1), 16);
+                    }
                 } else {
                     uint4v q;
                     q.x = pack_bf2(q0.x, q0.y);
