@@ -264,25 +264,30 @@ __device__ __forceinline__ void kc_worker(const KcArgs& a, char* lds, int tid, i
                                                   (64 * (wc2 & 1) + 16 * nb + l16) * 4) = acc[rb][nb][e];
         }
         __syncthreads();
-        const int col = n0 + 128 * hf + 16 * cg;
+        // A row's eight threads store one whole 128-byte line per instruction: thread cg takes the
+        // cg-th 16 bytes of every line of the row's 128-column piece (2 lines in bf16, 4 in fp32).
+        constexpr int kColsPerStore = kOutF32 ? 4 : 8, kLines = 128 / (8 * kColsPerStore);
 #pragma unroll
         for (int p = 0; p < kBM / kRowsPerPass; ++p) {
             const int row = cr + kRowsPerPass * p;
-            if (row < rows && col < a.C) {
-                const float4* src = reinterpret_cast<const float4*>(lds + row * kCRow + cg * 64);
-                const float4 q0 = src[0], q1 = src[1], q2 = src[2], q3 = src[3];
+            if (row >= rows) continue;
+#pragma unroll
+            for (int ln = 0; ln < kLines; ++ln) {
+                const int lc = 8 * kColsPerStore * ln + kColsPerStore * cg;      // column within the piece
+                const int col = n0 + 128 * hf + lc;
+                if (col >= a.C) continue;
+                const float4* src = reinterpret_cast<const float4*>(lds + row * kCRow + lc * 4);
                 const long long e = (m0 + row) * a.C + col;
                 if constexpr (kOutF32) {
-                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(a.c) + e);
-                    dst[0] = q0; dst[1] = q1; dst[2] = q2; dst[3] = q3;
+                    *reinterpret_cast<float4*>(static_cast<float*>(a.c) + e) = src[0];
                 } else {
                     auto pk = [](float lo, float hi) {
                         return static_cast<unsigned>(__builtin_bit_cast(unsigned short, static_cast<__bf16>(lo))) |
                                (static_cast<unsigned>(__builtin_bit_cast(unsigned short, static_cast<__bf16>(hi))) << 16);
                     };
-                    uint4* dst = reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.c) + e);
-                    dst[0] = make_uint4(pk(q0.x, q0.y), pk(q0.z, q0.w), pk(q1.x, q1.y), pk(q1.z, q1.w));
-                    dst[1] = make_uint4(pk(q2.x, q2.y), pk(q2.z, q2.w), pk(q3.x, q3.y), pk(q3.z, q3.w));
+                    const float4 q0 = src[0], q1 = src[1];
+                    *reinterpret_cast<uint4*>(static_cast<unsigned short*>(a.c) + e) =
+                        make_uint4(pk(q0.x, q0.y), pk(q0.z, q0.w), pk(q1.x, q1.y), pk(q1.z, q1.w));
                 }
             }
         }
