@@ -35,6 +35,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16/bf16 MFMA
 # value = FETCH_SIZE (KiB) x 2.0 (copy calibration) + WRITE_SIZE (KiB) x 1.0
 PROFILED_TRAFFIC = {
     ("config 2", "wkv6_prefill_bf16"): (int(262300 * 1024 * 2.0 + 135200 * 1024 * 1.0), "profiles/chunked_kernel_config2.md"),
+    ("config 3", "wkv6_prefill_bf16_split"): (int(1740783 * 1024 * 2.0 + 532536 * 1024 * 1.0), "profiles/chunked_kernel_configs_3_4_5.md"),
     ("config 2", "wkv6_finch_c2_prefill_bf16"): (int(327806 * 1024 * 2.0 + 135168 * 1024 * 1.0), "profiles/finch_c2_kernel_config2.md"),
     ("decode-step B=1024", "wkv6_decode_bf16"): (int(270381 * 1024 * 2.0 + 528416 * 1024 * 1.0), "profiles/decode_step_B1024.md"),
     ("decay-path front of config 2", "wkv6_decay_lora_input_bf16"): (int(126305 * 1024 * 2.0 + 6144 * 1024 * 1.0), "profiles/decay_input_config2_tokens.md"),

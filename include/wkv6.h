@@ -135,7 +135,7 @@ int wkv6_prefill_bf16_split(int B, int T, int H, int N,
  * return WKV6_ERR_WORKSPACE and enqueue nothing (B*segments*H <= 504 fits; config 3 with 8
  * segments uses 4.3 MB).  All calls on one GPU share that buffer, whatever their stream: calls
  * that overlap in time on one GPU race on it, so order them on one stream (or with events).
- * Nothing in it has to start at zero (pass 1 writes every entry the later passes read), and it
+ * Nothing in it has to start at zero (the first two passes write every entry that is read later), and it
  * keeps the last call's contents.  The buffer's address is looked up on a GPU's first call (one
  * hipGetSymbolAddress per device, no allocation); make that first call outside stream capture.
  * Arguments, results and errors otherwise as for wkv6_prefill_bf16_split.

@@ -429,14 +429,18 @@ int run_split(int B, int T, int H, int N, const void* r, const void* k, const vo
     a.segs = p.segs; a.T_last = p.last_len; a.unit_stride = 0; a.moments = nullptr;
     a.y = nullptr; a.lambda = nullptr; a.bw = nullptr;
     a.seg_stride = static_cast<long long>(p.seg_len) * H * N;
-    // pass 1: every segment from a zero state, no output: its local state and total decay
+    // pass 1: every segment but the last (nothing follows it) from a zero state, no output: its
+    // local state and total decay
     a.state_in = nullptr; a.out = nullptr; a.state_out = seg_state; a.decay_out = seg_decay;
+    a.segs_launched = p.segs - 1;
     if (wkv6::launch_chunked(a, wkv6::ChunkedMode::kStateOnly, s) != hipSuccess) return WKV6_ERR_LAUNCH;
-    // pass 2: the state entering every segment (in place) and the final state
-    if (wkv6::launch_combine_segments(B, H, p.segs, state_in, seg_state, seg_decay, state_out, s) != hipSuccess)
+    // pass 2: the state entering every segment (in place)
+    if (wkv6::launch_combine_segments(B, H, p.segs, state_in, seg_state, seg_decay, nullptr, false, s) != hipSuccess)
         return WKV6_ERR_LAUNCH;
-    // pass 3: the full computation of every segment from its true entering state
-    a.state_in = seg_state; a.out = out; a.state_out = nullptr; a.decay_out = nullptr;
+    // pass 3: the full computation of every segment from its true entering state; the last
+    // segment's workgroups leave the sequence's final state
+    a.segs_launched = 0;
+    a.state_in = seg_state; a.out = out; a.state_out = state_out; a.state_out_final = true; a.decay_out = nullptr;
     const wkv6::ChunkedMode mode = out_dtype == WKV6_DTYPE_F32 ? wkv6::ChunkedMode::kF32Out
                                                                : wkv6::ChunkedMode::kBf16Out;
     if (wkv6::launch_chunked(a, mode, s) != hipSuccess) return WKV6_ERR_LAUNCH;

@@ -280,6 +280,7 @@ struct Units {
     int nchunks;          // chunks per unit
     long long base0;      // element offset of the first unit's token 0 in r,k,v,x,out
     long long step;       // element offset between consecutive units of this workgroup
+    float* state_out;     // where final states go, indexed like state_in (nullptr: not written)
 };
 
 // Sum over the 8 lanes of an aligned group of 8 (every lane gets the total): neighbours, pairs,
@@ -990,8 +991,8 @@ __device__ __forceinline__ void consumer(const Args& a, char* lds_all, int lane,
             if (at.c == un.nchunks - 1) {
                 // the unit ends: its final state and, if asked for, its total decay
                 const long long unit = static_cast<long long>(un.first) + static_cast<long long>(at.ui) * un.stride;
-                if (a.state_out) {
-                    const __amdgpu_buffer_rsrc_t rs = state_rsrc(a.state_out, at.ui);
+                if (un.state_out) {
+                    const __amdgpu_buffer_rsrc_t rs = state_rsrc(un.state_out, at.ui);
 #pragma unroll
                     for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
@@ -1034,8 +1035,9 @@ __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
     }
     const int bs = unit / a.H;
     const int h = unit - bs * a.H;
-    const int b = bs / a.segs;
-    const int seg = bs - b * a.segs;
+    const int segs_launched = a.segs_launched > 0 ? a.segs_launched : a.segs;
+    const int b = bs / segs_launched;
+    const int seg = bs - b * segs_launched;
     const long long tok_stride = static_cast<long long>(a.H) * kHeadSize;
     const long long unit_base = static_cast<long long>(b) * a.batch_stride +
                                 static_cast<long long>(seg) * a.seg_stride +
@@ -1044,8 +1046,11 @@ __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
     // The workgroup's units: this one and, when the launch gave a stride (a multiple of H, whole
     // sequences only), every stride-th unit after it: same head, batch index advancing.
     Units un;
-    un.first = unit;
+    un.first = (b * a.segs + seg) * a.H + h;     // = unit when every segment has a workgroup
     un.stride = a.unit_stride;
+    un.state_out = a.state_out;
+    if (a.state_out_final)                       // [B][H] states, written by the last segment only
+        un.state_out = a.state_out && seg == a.segs - 1 ? a.state_out - static_cast<long long>(un.first - (b * a.H + h)) * 4096 : nullptr;
     un.count = 1;
     un.nchunks = (T + kChunk - 1) / kChunk;
     un.base0 = unit_base;
@@ -1064,7 +1069,7 @@ __global__ __launch_bounds__(kThreads) void chunked_kernel(Args a) {
 // Sequential fold over the segments of one (batch, head): 256 threads x 16 state entries.
 __global__ __launch_bounds__(256) void combine_kernel(int H, int segs, const float* state_in,
                                                       float* seg_state, const float* seg_decay,
-                                                      float* state_out) {
+                                                      float* state_out, bool fold_last) {
     const int unit = blockIdx.x;                 // batch * H + head
     const int b = unit / H;
     const int h = unit - b * H;
@@ -1082,6 +1087,11 @@ __global__ __launch_bounds__(256) void combine_kernel(int H, int segs, const flo
     for (int p = 0; p < segs; ++p) {
         const long long su = (static_cast<long long>(b) * segs + p) * H + h;
         float4* loc = reinterpret_cast<float4*>(seg_state + su * 4096) + 4 * t;
+        if (p == segs - 1 && !fold_last) {       // nothing follows: its pair was not produced
+#pragma unroll
+            for (int q = 0; q < 4; ++q) loc[q] = S[q];
+            break;
+        }
         const float d = seg_decay[su * kHeadSize + row];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -1091,7 +1101,7 @@ __global__ __launch_bounds__(256) void combine_kernel(int H, int segs, const flo
                                fmaf(d, S[q].w, l.w));
         }
     }
-    if (state_out) {
+    if (state_out && fold_last) {
         float4* so = reinterpret_cast<float4*>(state_out + static_cast<long long>(unit) * 4096) + 4 * t;
 #pragma unroll
         for (int q = 0; q < 4; ++q) so[q] = S[q];
@@ -1104,7 +1114,7 @@ struct ChunkedTag {};
 template <int kMode, bool kC2>
 hipError_t launch_mode(const Args& args, hipStream_t stream) {
     Args a = args;
-    long long units = static_cast<long long>(a.B) * a.segs * a.H;
+    long long units = static_cast<long long>(a.B) * (a.segs_launched > 0 ? a.segs_launched : a.segs) * a.H;
     a.unit_stride = 0;
     // With more (batch, head) units than compute units each workgroup takes several of them back to back.
     const int cus = compute_units();
@@ -1150,9 +1160,9 @@ hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream) {
 }
 
 hipError_t launch_combine_segments(int B, int H, int segs, const float* state_in, float* seg_state,
-                                   const float* seg_decay, float* state_out, hipStream_t stream) {
+                                   const float* seg_decay, float* state_out, bool fold_last, hipStream_t stream) {
     hipLaunchKernelGGL(combine_kernel, dim3(static_cast<unsigned>(B) * static_cast<unsigned>(H)),
-                       dim3(256), 0, stream, H, segs, state_in, seg_state, seg_decay, state_out);
+                       dim3(256), 0, stream, H, segs, state_in, seg_state, seg_decay, state_out, fold_last);
     return hipGetLastError();
 }
 

@@ -30,6 +30,10 @@ struct Args {
     int segs;
     int T_last;
     long long seg_stride;
+    int segs_launched = 0;    // 0: every segment has a workgroup.  n > 0: only the first n segments of each
+                              // sequence have one (the indexing by all `segs` stays)
+    bool state_out_final = false;   // with segs > 1: state_out is [B][H][N][N] and only the last segment's
+                              // workgroup writes it (the state the whole sequence leaves behind)
     float* decay_out;         // may be nullptr; [B*segs][H][N] product of all decays of the unit
     float* moments;           // kBf16OutMoments only: [B][H][T][2] per (batch, head, token): the sum of
                               // the head's N output values and their squared deviations from the
@@ -59,10 +63,13 @@ hipError_t launch_recurrent(const Args& a, bool in_bf16, bool out_bf16, hipStrea
 hipError_t launch_chunked(const Args& a, ChunkedMode mode, hipStream_t stream);
 
 // Token-split support: folds the per-segment (decay, local state) pairs of every (batch, head)
-// into the state entering each segment, in place in `seg_state` ([B*segs][H][N][N]); writes the
-// final state of the sequence to state_out when it is not nullptr.
+// into the state entering each segment, in place in `seg_state` ([B*segs][H][N][N]).  The pair of
+// the last segment is not read (nothing follows it): the first pass need not produce it, and the
+// final state of the sequence comes from the full pass over the last segment (state_out_final).
+// state_out, when not nullptr, receives the state entering the last segment's successor only if
+// `fold_last` is set (then the last pair is read too).
 hipError_t launch_combine_segments(int B, int H, int segs, const float* state_in, float* seg_state,
-                                   const float* seg_decay, float* state_out, hipStream_t stream);
+                                   const float* seg_decay, float* state_out, bool fold_last, hipStream_t stream);
 
 // GOLD key compression c = x W: x [M][D] bf16, w [D][D/16] bf16, c [M][D/16] bf16 or fp32.
 // D must be a multiple of 256 (16 output columns per MFMA block, an even number of 64-channel steps).
