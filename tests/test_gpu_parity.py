@@ -43,6 +43,16 @@ def test_recurrent_kernel_on_bf16_inputs(gpu_device):
     check("wkv6_prefill_bf16_recurrent", inp, TOL_F32)
 
 
+@pytest.mark.parametrize("T", [1, 6, 7, 15, 16, 17, 23, 24, 25, 40])
+def test_token_by_token_forms_on_both_sides_of_their_switch(gpu_device, T):
+    """The token-by-token entry points use a one-wave kernel below 16 tokens and a four-wave kernel
+    with 8-token blocks from 16 on: lengths around the switch, with whole and ragged last blocks."""
+    inp = make_inputs(scaled(CONFIGS[1], B=2, T=T, H=3, s0_std=0.4), seed=900 + T)
+    check("wkv6_prefill_f32", inp, TOL_F32, in_dtype=torch.float32)
+    inp = make_inputs(scaled(CONFIGS[2], B=2, T=T, H=3, s0_std=0.4), seed=950 + T)
+    check("wkv6_prefill_bf16_recurrent", inp, TOL_F32)
+
+
 # ------------------------------------------------------------------ chunked kernel, oracle-sized
 @pytest.mark.parametrize("T", [1, 2, 7, 8, 9, 15, 16, 17, 31, 33, 63, 64, 65, 127, 128, 129, 200, 1000])
 def test_chunked_lengths(gpu_device, T):
