@@ -27,7 +27,8 @@
 //               16x16x16 MFMA, so z = x_t + (x_{t-1} - x_t) * mix is formed in registers and fed
 //               straight into the product with A_omega; mix and z never touch LDS or HBM.
 //               The y accumulators (a lane: four consecutive outputs of its token per 16-column
-//               block) get their tanh and leave as 8- or 16-byte stores.
+//               block) get their tanh and leave through the wave's own piece of LDS as whole rows
+//               (1 % faster than 8-byte stores straight from the accumulator layout).
 // One workgroup per compute unit (134 KB of LDS, 128 registers per thread).
 //
 // Weight layouts are the ones an MFMA operand can be read from with the contraction index
@@ -316,23 +317,41 @@ __device__ __forceinline__ void di_worker(const DiArgs& a, char* lds, int lane, 
         __syncthreads();
     }
 
-    // yacc[nb][e] = pre-activation of output 16nb + 4g4 + e of token trow
-    if (trow < ntok) {
-        const long long m = static_cast<long long>(b) * a.T + t0 + trow;
+    // yacc[nb][e] = pre-activation of output 16nb + 4g4 + e of token trow.  The wave's 16 rows go
+    // through its own piece of LDS (free after the last barrier; this wave alone touches it), so that
+    // every store instruction writes whole rows: 8 (bf16) or 16 (fp32) lanes of 16 bytes per row.
+    constexpr int kYRow = kOuterRank * 4 + 16;                   // fp32 row + pad
+    char* mine = lds + w * 16 * kYRow;
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-            float yv[4];
+    for (int nb = 0; nb < 4; ++nb)
+        *reinterpret_cast<float4*>(mine + l16 * kYRow + (16 * nb + 4 * g4) * 4) =
+            make_float4(fast_tanh(yacc[nb][0]), fast_tanh(yacc[nb][1]), fast_tanh(yacc[nb][2]), fast_tanh(yacc[nb][3]));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const long long m0 = static_cast<long long>(b) * a.T + t0 + 16 * w;   // the wave's first token
+    if constexpr (kOutF32) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) yv[e] = fast_tanh(yacc[nb][e]);
-            const int col = 16 * nb + 4 * g4;
-            if constexpr (kOutF32) {
-                *reinterpret_cast<float4*>(static_cast<float*>(a.y) + m * kOuterRank + col) = make_float4(yv[0], yv[1], yv[2], yv[3]);
-            } else {
+        for (int p = 0; p < 4; ++p) {
+            const int row = 4 * p + (lane >> 4), c4 = 4 * (lane & 15);
+            if (16 * w + row < ntok)
+                *reinterpret_cast<float4*>(static_cast<float*>(a.y) + (m0 + row) * kOuterRank + c4) =
+                    *reinterpret_cast<const float4*>(mine + row * kYRow + c4 * 4);
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int row = 8 * p + (lane >> 3), c8 = 8 * (lane & 7);
+            if (16 * w + row < ntok) {
                 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
                 typedef float float2v __attribute__((ext_vector_type(2)));
-                const uint2v q = {__builtin_bit_cast(unsigned, __builtin_convertvector(float2v{yv[0], yv[1]}, bf16x2)),
-                                  __builtin_bit_cast(unsigned, __builtin_convertvector(float2v{yv[2], yv[3]}, bf16x2))};
-                *reinterpret_cast<uint2v*>(static_cast<unsigned short*>(a.y) + m * kOuterRank + col) = q;
+                const float4 lo = *reinterpret_cast<const float4*>(mine + row * kYRow + c8 * 4);
+                const float4 hi = *reinterpret_cast<const float4*>(mine + row * kYRow + c8 * 4 + 16);
+                const uint4v q = {__builtin_bit_cast(unsigned, __builtin_convertvector(float2v{lo.x, lo.y}, bf16x2)),
+                                  __builtin_bit_cast(unsigned, __builtin_convertvector(float2v{lo.z, lo.w}, bf16x2)),
+                                  __builtin_bit_cast(unsigned, __builtin_convertvector(float2v{hi.x, hi.y}, bf16x2)),
+                                  __builtin_bit_cast(unsigned, __builtin_convertvector(float2v{hi.z, hi.w}, bf16x2))};
+                *reinterpret_cast<uint4v*>(static_cast<unsigned short*>(a.y) + (m0 + row) * kOuterRank + c8) = q;
             }
         }
     }
