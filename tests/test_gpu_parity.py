@@ -252,6 +252,25 @@ def test_split_bf16_out_and_no_state_out(gpu_device):
     assert s is None and max_norm_err(o, o_ref) <= TOL_BF16 + BF16_OUT_ROUNDING
 
 
+def test_split_state_in_place_and_short_last_segment(gpu_device):
+    """state_out may be the state_in buffer: the fold reads the entering state before the full pass
+    of the last segment (shorter than the others here) writes the final one over it."""
+    inp = make_inputs(scaled(CONFIGS[4], B=2, T=1000, H=3, s0_std=0.4), seed=74)
+    o_ref, s_ref = wkv6_oracle(**inp)
+    B, T, H, N = inp["r"].shape
+    r, k, v, x = (to_dev(inp[n], torch.bfloat16) for n in "rkvx")
+    u = to_dev(inp["u"], torch.float32)
+    state = to_dev(inp["state_in"], torch.float32)
+    out = torch.full((B, T, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    segments = 3                                   # 352 + 352 + 296 tokens
+    nbytes = wkv.wkv6_split_workspace_bytes(B, T, H, N, segments)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    wkv.wkv6_prefill_bf16_split(B, T, H, N, r, k, v, x, u, state, out, state, wkv.WKV6_DTYPE_F32, segments, ws, nbytes)
+    torch.cuda.synchronize()
+    assert max_norm_err(out.cpu().numpy().astype(np.float64), o_ref) <= TOL_BF16
+    assert max_norm_err(state.cpu().numpy().astype(np.float64), s_ref) <= TOL_BF16
+
+
 # ------------------------------------------------------------------ full-size configs, every unit
 def _unit_slice(inp, b, h):
     one = {n: np.ascontiguousarray(inp[n][b:b + 1, :, h:h + 1]) for n in "rkvx"}
