@@ -110,10 +110,11 @@ int wkv6_prefill_bf16_strided(int B, int T, int H, int N,
 /*
  * Token-split variant for few (batch, head) units and long sequences (B*H well below the 256
  * compute units, e.g. one long context): the T axis is cut into `segments` pieces that run in
- * parallel.  Three passes are enqueued on `stream`: (1) every segment's local state and total
- * decay from a zero state, using k, v, x only; (2) a sequential fold over segments that turns
- * them into the state entering each segment (the recurrence is linear in the state: S_out =
- * diag(prod w) S_in + S_local); (3) the full computation of every segment from that state.
+ * parallel.  Three passes are enqueued on `stream`: (1) the local state and total decay of every
+ * segment but the last from a zero state, using k, v, x only; (2) a sequential fold over segments
+ * that turns them into the state entering each segment (the recurrence is linear in the state:
+ * S_out = diag(prod w) S_in + S_local); (3) the full computation of every segment from that
+ * state, the last segment leaving the final state in state_out.
  * Results equal the single-pass entry points up to rounding order.  `workspace` is caller-owned
  * device memory of at least wkv6_split_workspace_bytes() bytes, 16-byte aligned, used only
  * during the call's kernels; calls sharing a workspace must be ordered on one stream.
