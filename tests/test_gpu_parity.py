@@ -271,6 +271,43 @@ def test_split_state_in_place_and_short_last_segment(gpu_device):
     assert max_norm_err(state.cpu().numpy().astype(np.float64), s_ref) <= TOL_BF16
 
 
+def test_tensors_beyond_four_gib(gpu_device):
+    """Every tensor larger than 4 GiB (H = 544 heads, 65 536 tokens: 4.56 GB each), so byte offsets
+    inside a tensor pass 2^32 and a token row is 68 KiB: the kernel re-bases its 32-bit buffer
+    descriptors per chunk.  Inputs are drawn on the device (seeded); the units compared with the
+    oracle are the first head, one in the middle and the last one, whose rows sit at the far end."""
+    B, T, H, N = 1, 65536, 544, 64
+    gen = torch.Generator(device="cuda").manual_seed(4242)
+    def draw(scale, shift):
+        t = torch.empty((B, T, H, N), dtype=torch.bfloat16, device="cuda")
+        for t0 in range(0, T, 4096):                     # 0.57 GB of fp32 at a time
+            blk = torch.rand((B, 4096, H, N), generator=gen, device="cuda") * scale + shift
+            t[:, t0:t0 + 4096] = blk.to(torch.bfloat16)
+        return t
+    r, k, v = draw(2.0, -1.0), draw(2.0, -1.0), draw(2.0, -1.0)
+    x = draw(7.0, -8.0)                                  # w between exp(-exp(-1)) and nearly 1
+    u = (torch.rand((H, N), generator=gen, device="cuda") - 0.5).contiguous()
+    out = torch.full((B, T, H, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    s_out = torch.full((B, H, N, N), float("nan"), dtype=torch.float32, device="cuda")
+    assert r.numel() * 2 > (1 << 32)
+    print("tensors of %.2f GB each" % (r.numel() * 2 / 1e9), flush=True)
+    wkv.wkv6_prefill_bf16(B, T, H, N, r, k, v, x, u, None, out, s_out)
+    torch.cuda.synchronize()
+    for h in (0, 271, 543):
+        one = {n: t[:, :, h:h + 1].float().cpu().numpy() for n, t in (("r", r), ("k", k), ("v", v), ("x", x))}
+        o_ref, s_ref = wkv6_oracle(one["r"], one["k"], one["v"], one["x"], u[h:h + 1].cpu().numpy(), None)
+        o = out[:, :, h:h + 1].float().cpu().numpy().astype(np.float64)
+        s = s_out[:, h:h + 1].cpu().numpy().astype(np.float64)
+        eo, es = max_norm_err(o, o_ref), max_norm_err(s, s_ref)
+        print(f"head {h}: err_out={eo:.3e} err_state={es:.3e}", flush=True)
+        assert np.isfinite(o).all() and np.isfinite(s).all()
+        assert eo <= TOL_BF16 + BF16_OUT_ROUNDING and es <= TOL_BF16
+    # every row was written
+    assert bool(torch.isfinite(out[:, -1].float()).all()) and bool(torch.isfinite(out[:, 0].float()).all())
+    del r, k, v, x, out
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ full-size configs, every unit
 def _unit_slice(inp, b, h):
     one = {n: np.ascontiguousarray(inp[n][b:b + 1, :, h:h + 1]) for n in "rkvx"}
