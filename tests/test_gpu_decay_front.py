@@ -134,3 +134,34 @@ def test_full_size_every_token(gpu_device):
     assert max_norm_err(y32, ref) <= TOL_BF16
     y16 = run_front(fi, torch.bfloat16).float().cpu().numpy()
     assert np.array_equal(y16, round_to_bf16(y32))
+
+
+def test_input_beyond_four_gib(gpu_device):
+    """x of 4.83 GB (one sequence of 1 179 648 tokens of width 2048, drawn on the device from a seed): byte
+    offsets into x pass 2^32.  Windows of tokens at the start, in the middle and at the end are compared with
+    the oracle, each window's predecessor row given to the oracle as its x_prev."""
+    B, T, D = 1, 9216 * 128, 2048
+    fi = make_decay_front_inputs(scaled(CONFIGS[2], B=1, T=4, H=D // 64), seed=4321)      # weights and vectors
+    gen = torch.Generator(device="cuda").manual_seed(98)
+    x = torch.empty((B, T, D), dtype=torch.bfloat16, device="cuda")
+    for t0 in range(0, T, 65536):
+        x[:, t0:t0 + 65536] = torch.randn((B, 65536, D), generator=gen, device="cuda").to(torch.bfloat16)
+    assert x.numel() * 2 > (1 << 32)
+    xp = to_dev(fi["x_prev"], torch.bfloat16)
+    mu, lam = to_dev(fi["mu_x"], torch.float32), to_dev(fi["lam_d"], torch.float32)
+    a_d = to_dev(np.ascontiguousarray(fi["A_d"].T), torch.bfloat16)
+    b_d = to_dev(np.ascontiguousarray(fi["B_d"].T), torch.bfloat16)
+    a_w = to_dev(np.ascontiguousarray(fi["A_omega"].T), torch.bfloat16)
+    y = torch.full((B, T, 64), float("nan"), dtype=torch.float32, device="cuda")
+    wkv.wkv6_decay_lora_input_bf16(B, T, D, 32, 64, x, xp, mu, lam, a_d, b_d, a_w, y, wkv.WKV6_DTYPE_F32)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y).all())
+    for t0 in (0, (T // 2 // 128) * 128 + 100, T - 200):
+        rows = x[:, t0:t0 + 200].float().cpu().numpy()
+        prev = fi["x_prev"] if t0 == 0 else x[:, t0 - 1].float().cpu().numpy()
+        ref = decay_lora_input_numpy(rows, prev, fi["mu_x"], fi["lam_d"], fi["A_d"], fi["B_d"], fi["A_omega"])
+        err = max_norm_err(y[:, t0:t0 + 200].cpu().numpy(), ref)
+        print(f"tokens {t0}..{t0 + 199}: err={err:.3e}", flush=True)
+        assert err <= TOL_BF16
+    del x, y
+    torch.cuda.empty_cache()

@@ -73,3 +73,27 @@ def test_full_size_every_row(gpu_device, M, D):
     assert err <= 1e-5 and rows.max() <= 1e-5
     c16 = run(x, w, torch.bfloat16)
     assert np.array_equal(c16, round_to_bf16(c32))
+
+
+def test_input_beyond_four_gib(gpu_device):
+    """x of 4.83 GB (1 179 648 tokens of width 2048, drawn on the device from a seed): byte offsets into x
+    pass 2^32.  The first, a middle and the last row tile are compared with the oracle."""
+    M, D = 9216 * 128, 2048
+    _, w = make_key_compress_inputs(16, D, seed=77)
+    gen = torch.Generator(device="cuda").manual_seed(99)
+    x = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+    for m0 in range(0, M, 65536):
+        x[m0:m0 + 65536] = torch.randn((65536, D), generator=gen, device="cuda").to(torch.bfloat16)
+    assert x.numel() * 2 > (1 << 32)
+    wd = to_dev(w, torch.bfloat16)
+    c = torch.full((M, D // 16), float("nan"), dtype=torch.float32, device="cuda")
+    wkv.wkv6_key_compress_bf16(M, D, x, wd, c, wkv.WKV6_DTYPE_F32)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(c).all())
+    for m0 in (0, (M // 2 // 128) * 128 + 64, M - 128):
+        ref = key_compress_oracle(x[m0:m0 + 128].float().cpu().numpy(), w)
+        err = max_norm_err(c[m0:m0 + 128].cpu().numpy(), ref)
+        print(f"rows {m0}..{m0 + 127}: err={err:.3e}", flush=True)
+        assert err <= 1e-5
+    del x, c
+    torch.cuda.empty_cache()
